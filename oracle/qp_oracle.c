@@ -1,0 +1,358 @@
+/*
+ * CPU oracle for the activation-compression path of QuantPipe
+ * (statistics -> ACIQ clipping -> DS-ACIQ directed search -> clip + uniform
+ * quantize + bit-pack -> unpack + dequantize).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, sequential
+ * statement of what the path computes, written from the paper so that the HIP
+ * library can be compared with it element by element.  It shares no code,
+ * header, table or constant with the HIP library, and only the tests, the smoke
+ * check and the benchmark's CPU-baseline leg may call it.
+ *
+ * Arithmetic: every reduction is a sequential fp64 sum in index order.  The
+ * per-element quantization arithmetic is fp32 in a fixed operation order (so
+ * that integer codes are well defined); build with -ffp-contract=off so that
+ * no multiply-add is fused except where fmaf() is written.
+ *
+ * Pins (see the CPU tests): statistics against closed forms and numpy; the
+ * histogram against numpy.histogram on dyadic data; the Laplace constant
+ * against scipy's Lambert W, a brute-force minimum of the noise model and the
+ * 2/3/4-bit constants printed in the ACIQ paper the method cites; the Gaussian
+ * constant against a brute-force minimum of numerically integrated noise; the
+ * search against an independent numpy sweep on tiny tensors; quantize against
+ * invariants and the 8-bit identity; pack/unpack against numpy.packbits and
+ * uint8/uint16 views; dequantize against the fp64 definition.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ---- plain-data records (the oracle's own; the Python side mirrors them) ---- */
+
+typedef struct {
+    uint64_t n;            /* element count */
+    uint64_t n_nonfinite;  /* NaN or +-Inf elements */
+    double mean;           /* mu = (1/N) sum x */
+    double mad;            /* (1/N) sum |x - mu|   : the Laplace scale b_E */
+    double abs_mean;       /* (1/N) sum |x|        : the paper's literal b_E formula */
+    double var;            /* (1/N) sum (x - mu)^2 : population variance */
+    double min;
+    double max;
+    uint32_t nbins;
+    uint32_t peak_count;   /* largest histogram count */
+    double peak_density;   /* peak_count / (N * bin width) */
+    double b_r;            /* 1 / (2 * peak_density) */
+} orc_stats_t;
+
+typedef struct {
+    uint32_t bits;
+    uint32_t levels;       /* L = 2^bits - 1 */
+    uint64_t n;
+    float lo, hi, scale, inv_scale;
+} orc_qparams_t;
+
+typedef struct {
+    double b_e, b_r, b_star, alpha_star, mse_aciq, mse_star;
+    uint32_t j_star;
+    uint32_t t_steps;
+} orc_search_result_t;
+
+enum { ORC_LAPLACE = 0, ORC_GAUSS = 1 };
+
+static int orc_bits_ok(uint32_t bits)
+{
+    return bits == 2 || bits == 3 || bits == 4 || bits == 6 || bits == 8 || bits == 16;
+}
+
+/* ---- bf16 -> fp32: exact widening (the 16 bits become the top half) ---- */
+
+void orc_widen_bf16(const uint16_t *h, uint64_t n, float *out)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t u = (uint32_t)h[i] << 16;
+        memcpy(&out[i], &u, 4);
+    }
+}
+
+/* ---- Step 1: statistics and histogram (Sec. 3: L(mu, b); b_E; D_R; b_R) ----
+ *
+ * mu and b_E: the activation is modelled as Laplace L(mu, b) (Sec. 3, ACIQ
+ * paragraph); b is its mean absolute deviation about mu.  The paper's printed
+ * estimate sum|X|/N (Sec. 3, Directed Search) is abs_mean; they agree at mu=0.
+ * D_R: nbins equal-width bins over [min, max]; bin index in fp32.
+ * b_R = 1 / (2 max(D_R)) with D_R as a density (Sec. 3, after Eq. 1): the
+ * Laplace pdf peaks at 1/(2b).
+ * Returns 0, or 1 if any element is NaN/Inf (then the other fields are not
+ * meaningful).  hist may be NULL.
+ */
+int orc_stats(const float *x, uint64_t n, uint32_t nbins, orc_stats_t *out, uint32_t *hist)
+{
+    memset(out, 0, sizeof *out);
+    out->n = n;
+    out->nbins = nbins;
+    if (n == 0 || nbins == 0) return 2;
+
+    double sum = 0.0, sum_abs = 0.0;
+    float mn = INFINITY, mx = -INFINITY;
+    uint64_t bad = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        float v = x[i];
+        if (!isfinite(v)) { ++bad; continue; }
+        sum += (double)v;
+        sum_abs += fabs((double)v);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    out->n_nonfinite = bad;
+    if (bad) return 1;
+
+    double mean = sum / (double)n;
+    double dev = 0.0, sq = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        double d = (double)x[i] - mean;
+        dev += fabs(d);
+        sq += d * d;
+    }
+    out->mean = mean;
+    out->abs_mean = sum_abs / (double)n;
+    out->mad = dev / (double)n;
+    out->var = sq / (double)n;
+    out->min = (double)mn;
+    out->max = (double)mx;
+
+    uint32_t peak = 0;
+    if (mx == mn) {
+        /* one distinct value: everything sits in bin 0 and the density peak is unbounded */
+        if (hist) { memset(hist, 0, (size_t)nbins * 4); hist[0] = (uint32_t)n; }
+        out->peak_count = (uint32_t)n;
+        out->peak_density = 0.0;
+        out->b_r = 0.0;
+        return 0;
+    }
+    /* fp32: one subtraction, one division, then per element one subtraction and one product */
+    float range = mx - mn;
+    float w_inv = (float)nbins / range;
+    uint32_t *h = hist;
+    uint32_t local[4096];
+    if (!h) { if (nbins > 4096) return 2; h = local; }
+    memset(h, 0, (size_t)nbins * 4);
+    for (uint64_t i = 0; i < n; ++i) {
+        float t = (x[i] - mn) * w_inv;
+        uint32_t idx;
+        if (!(t >= 0.0f)) idx = 0;                       /* also NaN (0 * inf) */
+        else if (t >= (float)nbins) idx = nbins - 1;     /* x == max, or overflow */
+        else idx = (uint32_t)t;                          /* truncation == floor for t >= 0 */
+        ++h[idx];
+    }
+    for (uint32_t b = 0; b < nbins; ++b)
+        if (h[b] > peak) peak = h[b];
+    out->peak_count = peak;
+    double binw = ((double)mx - (double)mn) / (double)nbins;
+    out->peak_density = (double)peak / ((double)n * binw);
+    out->b_r = 1.0 / (2.0 * out->peak_density);
+    return 0;
+}
+
+/* ---- Step 2a: the ACIQ constants -------------------------------------------
+ *
+ * Laplace (the paper's model, Sec. 3: alpha = F(q) b).  The ACIQ noise model for
+ * unit scale is clipping noise 2 e^{-a} plus rounding noise a^2 / (3 4^q); its
+ * stationary point satisfies a e^a = 3 4^q, so F(q) = W0(3 4^q), W0 the
+ * principal Lambert W.
+ */
+double orc_lambert_w0(double z)
+{
+    if (!(z >= 0.0)) return NAN;
+    if (z == 0.0) return 0.0;
+    double w = (z < 3.0) ? z / (1.0 + z) * 1.2 : log(z) - log(log(z));
+    for (int it = 0; it < 100; ++it) {
+        double ew = exp(w);
+        double f = w * ew - z;
+        /* Halley step for f(w) = w e^w - z */
+        double denom = ew * (w + 1.0) - (w + 2.0) * f / (2.0 * w + 2.0);
+        double wn = w - f / denom;
+        if (fabs(wn - w) <= 1e-16 * fabs(wn)) { w = wn; break; }
+        w = wn;
+    }
+    return w;
+}
+
+double orc_laplace_F(uint32_t bits)
+{
+    return orc_lambert_w0(3.0 * pow(4.0, (double)bits));
+}
+
+/* Gaussian variant: for unit sigma the clipping noise is
+ * 2[(1+a^2) Q(a) - a phi(a)] and the rounding noise a^2/(3 4^q); the stationary
+ * point satisfies phi(a) - a Q(a) = a / (6 4^q).  Solved by bisection. */
+double orc_gauss_G(uint32_t bits)
+{
+    const double inv_sqrt_2pi = 0.39894228040143267794;
+    double rhs_coef = 1.0 / (6.0 * pow(4.0, (double)bits));
+    double lo = 0.0, hi = 40.0;
+    for (int it = 0; it < 200; ++it) {
+        double a = 0.5 * (lo + hi);
+        double phi = inv_sqrt_2pi * exp(-0.5 * a * a);
+        double q = 0.5 * erfc(a / sqrt(2.0));
+        double f = phi - a * q - a * rhs_coef;   /* decreasing in a */
+        if (f > 0.0) lo = a; else hi = a;
+    }
+    return 0.5 * (lo + hi);
+}
+
+/* alpha = F(q) * b_E (Laplace) or G(q) * sigma (Gaussian). */
+int orc_aciq_alpha(const orc_stats_t *st, uint32_t bits, int dist, double *alpha)
+{
+    if (!orc_bits_ok(bits)) return 2;
+    if (dist == ORC_LAPLACE) *alpha = orc_laplace_F(bits) * st->mad;
+    else if (dist == ORC_GAUSS) *alpha = orc_gauss_G(bits) * sqrt(st->var);
+    else return 2;
+    return 0;
+}
+
+/* ---- quantization grid: [center - alpha, center + alpha], 2^k levels with the
+ * two end points representable ("equal intervals", Sec. 3) ---- */
+int orc_make_qparams(double center, double alpha, uint32_t bits, uint64_t n, orc_qparams_t *q)
+{
+    if (!orc_bits_ok(bits)) return 2;
+    float a32 = (float)alpha;
+    float c32 = (float)center;
+    q->bits = bits;
+    q->levels = (1u << bits) - 1u;
+    q->n = n;
+    q->lo = (float)((double)c32 - (double)a32);
+    q->hi = (float)((double)c32 + (double)a32);
+    double range = (double)q->hi - (double)q->lo;
+    if (q->hi == q->lo) {
+        q->scale = 0.0f;
+        q->inv_scale = 0.0f;
+    } else {
+        q->scale = (float)(range / (double)q->levels);
+        q->inv_scale = (float)((double)q->levels / range);
+    }
+    return 0;
+}
+
+/* ---- Step 3: clip + uniform quantize (Sec. 3: clamp outliers, equal intervals) ---- */
+uint32_t orc_quant_one(float x, const orc_qparams_t *q)
+{
+    float xc = fminf(fmaxf(x, q->lo), q->hi);     /* NaN -> lo */
+    float d = xc - q->lo;                         /* fp32 subtraction */
+    float t = d * q->inv_scale;                   /* fp32 product, not fused */
+    float r = rintf(t);                           /* round half to even */
+    float L = (float)q->levels;
+    if (!(r >= 0.0f)) r = 0.0f;
+    if (r > L) r = L;
+    return (uint32_t)r;
+}
+
+/* ---- Step 4: dequantize: lo + c*scale rounded once to fp32 ---- */
+float orc_dequant_one(uint32_t c, const orc_qparams_t *q)
+{
+    return fmaf((float)c, q->scale, q->lo);
+}
+
+void orc_quantize(const float *x, uint64_t n, const orc_qparams_t *q, uint32_t *codes)
+{
+    for (uint64_t i = 0; i < n; ++i) codes[i] = orc_quant_one(x[i], q);
+}
+
+void orc_dequantize(const uint32_t *codes, uint64_t n, const orc_qparams_t *q, float *y)
+{
+    for (uint64_t i = 0; i < n; ++i) y[i] = orc_dequant_one(codes[i], q);
+}
+
+/* ---- wire format: code i occupies stream bits [i k, i k + k), least significant
+ * bit first; stream bit p is bit (p mod 8) of byte (p div 8); the length is a
+ * whole number of 32-bit words and unused tail bits are zero. ---- */
+uint64_t orc_packed_bytes(uint64_t n, uint32_t bits)
+{
+    if (!orc_bits_ok(bits)) return 0;
+    return 4u * ((n * (uint64_t)bits + 31u) / 32u);
+}
+
+int orc_pack(const uint32_t *codes, uint64_t n, uint32_t bits, uint8_t *out, uint64_t out_bytes)
+{
+    uint64_t need = orc_packed_bytes(n, bits);
+    if (need == 0 || out_bytes < need) return 2;
+    memset(out, 0, need);
+    for (uint64_t i = 0; i < n; ++i)
+        for (uint32_t b = 0; b < bits; ++b)
+            if ((codes[i] >> b) & 1u) {
+                uint64_t p = i * bits + b;
+                out[p >> 3] |= (uint8_t)(1u << (p & 7u));
+            }
+    return 0;
+}
+
+int orc_unpack(const uint8_t *in, uint64_t n, uint32_t bits, uint32_t *codes)
+{
+    if (!orc_bits_ok(bits)) return 2;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t c = 0;
+        for (uint32_t b = 0; b < bits; ++b) {
+            uint64_t p = i * bits + b;
+            c |= (uint32_t)((in[p >> 3] >> (p & 7u)) & 1u) << b;
+        }
+        codes[i] = c;
+    }
+    return 0;
+}
+
+/* sum over the tensor of (x - dequant(quant(x)))^2: fp32 error, fp64 square and sum */
+double orc_sq_error(const float *x, uint64_t n, const orc_qparams_t *q)
+{
+    double s = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        float xh = orc_dequant_one(orc_quant_one(x[i], q), q);
+        float e = x[i] - xh;
+        s += (double)e * (double)e;
+    }
+    return s;
+}
+
+/* ---- Step 2b: DS-ACIQ directed search (Sec. 3, Eq. 1) -----------------------
+ *
+ * Candidates b_j = b_E + j (b_R - b_E)/t, j = 0..t, walk from the ACIQ estimate
+ * towards the bound given by the real peak, in whichever direction that is.
+ * Each is scored by the quantization error on the real tensor with
+ * alpha_j = F(q) b_j and the grid centred on mu.  The lowest score wins and ties
+ * go to the smallest j, so b_E is kept unless something is strictly better.
+ * A bound that is zero, negative or not finite (or b_E <= 0) collapses the grid
+ * onto b_E.  scores (t+1 doubles) receives the sums of squared errors.
+ */
+int orc_dsaciq_search(const float *x, uint64_t n, const orc_stats_t *st, uint32_t bits,
+                      uint32_t t_steps, orc_search_result_t *res, orc_qparams_t *best_q,
+                      double *scores)
+{
+    if (!orc_bits_ok(bits) || t_steps == 0 || n == 0) return 2;
+    double F = orc_laplace_F(bits);
+    double b_e = st->mad, b_r = st->b_r;
+    double step = (b_r - b_e) / (double)t_steps;
+    if (!(b_e > 0.0) || !(b_r > 0.0) || !isfinite(b_r) || !isfinite(b_e) || !isfinite(step))
+        step = 0.0;
+    uint32_t best_j = 0;
+    double best = 0.0, first = 0.0;
+    for (uint32_t j = 0; j <= t_steps; ++j) {
+        double b_j = b_e + (double)j * step;
+        double alpha = F * b_j;
+        orc_qparams_t q;
+        orc_make_qparams(st->mean, alpha, bits, n, &q);
+        double s = orc_sq_error(x, n, &q);
+        if (scores) scores[j] = s;
+        if (j == 0) first = s;
+        if (j == 0 || s < best) { best = s; best_j = j; }
+    }
+    double b_star = b_e + (double)best_j * step;
+    res->b_e = b_e;
+    res->b_r = b_r;
+    res->b_star = b_star;
+    res->alpha_star = F * b_star;
+    res->j_star = best_j;
+    res->t_steps = t_steps;
+    res->mse_aciq = first / (double)n;   /* j = 0 is plain ACIQ */
+    res->mse_star = best / (double)n;
+    if (best_q) orc_make_qparams(st->mean, res->alpha_star, bits, n, best_q);
+    return 0;
+}
