@@ -1,0 +1,207 @@
+/*
+ * quantpipe.h -- C ABI of the MI355X (gfx950) activation-compression library.
+ *
+ * The library implements the data-parallel part of QuantPipe's PDA module
+ * (arXiv 2211.04515, Sec. 3): the tensor that leaves a pipeline stage is
+ * compressed to q-bit integer codes before it crosses the stage boundary and
+ * is expanded back to fp32 on the other side.  Four steps:
+ *
+ *   1. qp_stats           per-tensor statistics: mean mu, mean absolute deviation
+ *                         (the Laplace scale b_E), variance, min, max, and a
+ *                         histogram D_R whose peak gives the search bound b_R;
+ *   2. qp_aciq_alpha      ACIQ clipping threshold alpha = F(q) b       (host only)
+ *      qp_dsaciq_search   DS-ACIQ directed search for b* in [b_E, b_R] (Eq. 1);
+ *   3. qp_quant_pack      clip to [mu-alpha, mu+alpha], uniform quantize, bit-pack;
+ *   4. qp_unpack_dequant  unpack and dequantize.
+ *
+ * Conventions
+ *   - Pointers named *_dev are DEVICE pointers (HIP global memory on the current
+ *     device); pointers named *_host, and all struct pointers unless named *_dev,
+ *     are HOST pointers.  The caller owns every buffer.  The library allocates
+ *     no device memory and keeps no global state; two calls may run
+ *     concurrently if they use different streams AND different workspaces.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - x_dev, packed_dev, y_dev and ws_dev must be 16-byte aligned; ws_dev needs
+ *     qp_workspace_bytes() bytes.  The workspace needs no initialisation.
+ *   - Element types: QP_F32 (IEEE binary32) or QP_BF16 (bfloat16; widened exactly
+ *     to fp32 in registers).  Tensors are contiguous and treated as flat, 1 <= n < 2^32.
+ *   - Bitwidths: 2, 3, 4, 6, 8, 16.
+ *   - Functions that return results to the host synchronise `stream` before
+ *     returning; the *_async / *_dev forms never synchronise and leave their
+ *     results in the workspace (offsets from qp_ws_offset()).
+ *   - Errors are return codes only (no exceptions cross this boundary):
+ *       QP_EINVAL     null pointer, n == 0 or too large, bad bitwidth / dtype /
+ *                     nbins / search configuration, misaligned device pointer,
+ *                     qparams->n != n;
+ *       QP_ENOSPC     output buffer or workspace too small;
+ *       QP_EHIP       a HIP call or kernel launch failed;
+ *       QP_ENONFINITE qp_stats found NaN or Inf in the tensor (the statistics
+ *                     are then not meaningful; n_nonfinite is valid).
+ *
+ * Wire format of the packed buffer (the paper leaves it open; Sec. 3 only fixes
+ * the size, N q / 8 bytes: "compressed by 4x using 8-bit quantization"):
+ * code i occupies bits [i q, i q + q) of a bit stream, least significant bit
+ * first; stream bit p is bit (p mod 32) of little-endian 32-bit word (p div 32).
+ * The buffer is 4*ceil(N q / 32) bytes; unused tail bits are written as zero.
+ * The 32-byte qp_qparams_t travels beside the buffer.
+ */
+#ifndef QUANTPIPE_H
+#define QUANTPIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { QP_OK = 0, QP_EINVAL = -1, QP_ENOSPC = -2, QP_EHIP = -3, QP_ENONFINITE = -4 } qp_status;
+typedef enum { QP_F32 = 0, QP_BF16 = 1 } qp_dtype;
+typedef enum { QP_LAPLACE = 0, QP_GAUSS = 1 } qp_dist;
+
+/* Per-tensor statistics (Sec. 3: the activation is modelled as Laplace L(mu, b)). */
+typedef struct {
+    uint64_t n;            /* element count */
+    uint64_t n_nonfinite;  /* NaN / Inf elements found */
+    double   mean;         /* mu */
+    double   mad;          /* (1/N) sum |x - mu|: the Laplace scale b_E */
+    double   abs_mean;     /* (1/N) sum |x|: the estimate as printed in Sec. 3 (equals mad when mu = 0) */
+    double   var;          /* (1/N) sum (x - mu)^2 */
+    double   min, max;
+    uint32_t nbins;        /* histogram D_R: nbins equal bins over [min, max] */
+    uint32_t peak_count;   /* max(D_R) as a count */
+    double   peak_density; /* peak_count / (N * bin width) */
+    double   b_r;          /* search bound b_R = 1 / (2 max(D_R)) (after Eq. 1); 0 if min == max */
+} qp_stats_t;
+
+/* What the receiver needs besides the packed buffer. */
+typedef struct {
+    uint32_t bits;
+    uint32_t reserved;     /* written as 0 */
+    uint64_t n;
+    float    lo, hi;       /* clipping range [mu - alpha, mu + alpha] rounded to fp32 */
+    float    scale;        /* (hi - lo) / (2^bits - 1); 0 if hi == lo */
+    float    inv_scale;    /* (2^bits - 1) / (hi - lo); 0 if hi == lo */
+} qp_qparams_t;
+
+/* Directed-search configuration.  The paper sets t_steps = 100 (Sec. 3). */
+typedef struct {
+    uint32_t t_steps;          /* 1..1023: candidates j = 0..t_steps */
+    uint32_t cands_per_round;  /* 1..32: candidates scored per pass over the tensor; never changes results */
+    uint32_t nbins;            /* kept with the configuration for callers; the search itself does not use it */
+    uint32_t dist;             /* must be QP_LAPLACE (the paper's model) */
+} qp_search_cfg_t;
+
+typedef struct {
+    double   b_e, b_r;         /* the two ends of the search interval */
+    double   b_star;           /* winning scale */
+    double   alpha_star;       /* F(q) * b_star */
+    double   mse_aciq;         /* mean squared quantization error at j = 0 (plain ACIQ) */
+    double   mse_star;         /* ... at the winner; <= mse_aciq */
+    uint32_t j_star;           /* winning grid index (0 = ACIQ kept) */
+    uint32_t t_steps;
+} qp_search_result_t;
+
+/* Regions of the workspace that the *_async forms leave results in. */
+typedef enum {
+    QP_WS_STATS = 0,     /* qp_stats_t */
+    QP_WS_RESULT = 1,    /* qp_search_result_t */
+    QP_WS_QPARAMS = 2,   /* qp_qparams_t of the search winner */
+    QP_WS_HIST = 3,      /* uint32_t[nbins] */
+    QP_WS_CANDS = 4,     /* per candidate {float lo, hi, scale, inv_scale} */
+    QP_WS_SCORES = 5     /* double[t_steps + 1]: sums of squared errors */
+} qp_ws_region;
+
+/* ---- sizes (host, pure) ---------------------------------------------------- */
+
+/* Bytes of the packed buffer for n codes of `bits` bits: 4*ceil(n*bits/32); 0 if bits is invalid. */
+size_t qp_packed_bytes(uint64_t n, uint32_t bits);
+
+/* Bytes of device workspace needed by qp_stats / qp_dsaciq_search for an n-element
+ * tensor under cfg (NULL = defaults: t_steps 100, cands_per_round 32).  0 on bad arguments. */
+size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg);
+
+/* Byte offset of a region inside the workspace; (size_t)-1 for an unknown region. */
+size_t qp_ws_offset(qp_ws_region region);
+
+/* Fills cfg with the defaults {100, 32, 2048, QP_LAPLACE}. */
+void qp_default_search_cfg(qp_search_cfg_t *cfg);
+
+/* ---- step 1: statistics (Sec. 3: mu and b of L(mu, b); b_E; histogram D_R; b_R) ----
+ * Two passes over x_dev (the mean must be known before |x - mu|, and min/max before
+ * the histogram).  fp64 accumulation, deterministic reduction order.  nbins in [16, 4096].
+ * qp_stats copies the result to *out_host and returns QP_ENONFINITE if NaN/Inf was seen.
+ * qp_stats_async leaves it at QP_WS_STATS (and the histogram at QP_WS_HIST). */
+qp_status qp_stats(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t nbins,
+                   void *ws_dev, size_t ws_bytes, void *stream, qp_stats_t *out_host);
+qp_status qp_stats_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t nbins,
+                         void *ws_dev, size_t ws_bytes, void *stream);
+
+/* ---- step 2a: ACIQ threshold (Sec. 3: alpha = F(q) * b) -- host only, pure ----
+ * Laplace: alpha = W0(3 * 4^bits) * stats->mad, W0 the principal Lambert W (the
+ * stationary point of ACIQ's clipping + rounding noise model).  Gaussian:
+ * alpha = G(bits) * sqrt(stats->var) with G from the matching Gaussian noise model. */
+qp_status qp_aciq_alpha(const qp_stats_t *stats, uint32_t bits, qp_dist dist, double *alpha_out);
+
+/* The constant alone: F(bits) for QP_LAPLACE, G(bits) for QP_GAUSS; NaN on bad arguments. */
+double qp_aciq_constant(uint32_t bits, qp_dist dist);
+
+/* Quantization grid for the range [center - alpha, center + alpha] with 2^bits levels,
+ * both end points representable ("equal intervals for rounding", Sec. 3).  Host only, pure.
+ * Naive PTQ (Sec. 3) is center = (min+max)/2, alpha = (max-min)/2. */
+qp_status qp_make_qparams(double center, double alpha, uint32_t bits, uint64_t n, qp_qparams_t *out);
+
+/* ---- step 2b: DS-ACIQ directed search (Sec. 3, Eq. 1) -------------------------
+ * Candidates b_j = b_E + j (b_R - b_E) / t, j = 0..t, with b_E = stats->mad and
+ * b_R = stats->b_r, whichever way that points.  Each is scored by the squared
+ * quantization error on the real tensor, sum_i (x_i - dequant(quant(x_i)))^2, with
+ * alpha_j = F(q) b_j centred on stats->mean, using exactly the arithmetic of
+ * qp_quant_pack / qp_unpack_dequant (fp32 per element, fp64 sums).  The lowest score
+ * wins, ties go to the smallest j, so b_E is kept unless something is strictly better.
+ * A bound that is zero, negative or not finite collapses the grid onto b_E (j* = 0).
+ * The tensor is read once per round of cfg->cands_per_round candidates.
+ * qp_dsaciq_search returns the result and the winner's grid to the host (either may be
+ * NULL); the async form takes the statistics that qp_stats_async left in the same
+ * workspace and leaves QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES there. */
+qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats,
+                           uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
+                           void *stream, qp_search_result_t *res_host, qp_qparams_t *qparams_out_host);
+qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
+                                 const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream);
+
+/* ---- step 3: clip + uniform quantize + bit-pack (Sec. 3: ACIQ clipping, then PTQ) ----
+ * c_i = rne((min(max(x_i, lo), hi) - lo) * inv_scale) clamped to [0, 2^bits - 1]
+ * (fp32: one subtraction, one product, round half to even; NaN -> code 0), written in
+ * the wire format above.  Asynchronous on `stream`.  packed_bytes is the capacity of
+ * packed_dev (>= qp_packed_bytes(n, bits), else QP_ENOSPC).
+ * The _dev form reads the qp_qparams_t from device memory (e.g. QP_WS_QPARAMS) and
+ * needs the bitwidth on the host to choose the kernel; the record's n and bits must match. */
+qp_status qp_quant_pack(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_qparams_t *qparams,
+                        void *packed_dev, size_t packed_bytes, void *stream);
+qp_status qp_quant_pack_dev(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
+                            const qp_qparams_t *qparams_dev, void *packed_dev, size_t packed_bytes,
+                            void *stream);
+
+/* ---- step 4: unpack + dequantize (the receiving stage consumes fp32 again) ----
+ * y_i = fma((float)c_i, scale, lo): lo + c*scale rounded once to fp32.  Asynchronous.
+ * n must equal qparams->n; packed_bytes >= qp_packed_bytes(n, bits). */
+qp_status qp_unpack_dequant(const void *packed_dev, size_t packed_bytes, const qp_qparams_t *qparams,
+                            float *y_dev, uint64_t n, void *stream);
+qp_status qp_unpack_dequant_dev(const void *packed_dev, size_t packed_bytes, uint32_t bits,
+                                const qp_qparams_t *qparams_dev, float *y_dev, uint64_t n, void *stream);
+
+/* ---- whole sender side without a host round trip ------------------------------
+ * stats -> directed search -> quantize + pack, all on `stream`, nothing copied to the
+ * host.  If qparams_out_dev is not NULL the winner's record is also copied there
+ * (device to device) so that it can travel with the payload. */
+qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
+                            const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
+                            void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev,
+                            void *stream);
+
+const char *qp_strerror(qp_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUANTPIPE_H */

@@ -1,0 +1,285 @@
+// The C ABI: argument checks, host-side scalar work (ACIQ constants, quantization grid),
+// kernel launches, result copies.  Every per-element step runs in the HIP kernels; there
+// is no CPU fallback.
+#include <cmath>
+#include <cstring>
+
+#include "qp_common.hpp"
+
+using namespace qp;
+
+namespace {
+
+bool bits_ok(uint32_t b) { return b == 2 || b == 3 || b == 4 || b == 6 || b == 8 || b == 16; }
+bool dtype_ok(int d) { return d == QP_F32 || d == QP_BF16; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+constexpr uint64_t kMaxN = 0xffffffffull;   // histogram counts and block partial counters are 32-bit
+
+// Principal Lambert W for z >= e: Newton on g(w) = w + ln w - ln z (well conditioned for large z).
+double lambert_w0_large(double z)
+{
+    const double lz = std::log(z);
+    double w = lz - std::log(lz);
+    for (int i = 0; i < 64; ++i) {
+        const double g = w + std::log(w) - lz;
+        const double wn = w - g / (1.0 + 1.0 / w);
+        if (std::fabs(wn - w) <= 4e-16 * std::fabs(wn)) return wn;
+        w = wn;
+    }
+    return w;
+}
+
+// Laplace: the minimiser of 2 e^{-a} + a^2/(3 4^q) satisfies a e^a = 3 4^q.
+double laplace_constant(uint32_t bits) { return lambert_w0_large(3.0 * std::ldexp(1.0, 2 * (int)bits)); }
+
+// Gaussian: the minimiser of 2[(1+a^2)Q(a) - a phi(a)] + a^2/(3 4^q) satisfies
+// phi(a) - a Q(a) = a / (6 4^q).  Safeguarded Newton: the left side minus the right is convex
+// and decreasing, its derivative is -Q(a) - 1/(6 4^q).
+double gauss_constant(uint32_t bits)
+{
+    const double k = 1.0 / (6.0 * std::ldexp(1.0, 2 * (int)bits));
+    const double c = 0.3989422804014326779399461;   // 1/sqrt(2 pi)
+    double a = 1.0;
+    for (int i = 0; i < 200; ++i) {
+        const double phi = c * std::exp(-0.5 * a * a);
+        const double Q = 0.5 * std::erfc(a * 0.7071067811865475244008444);
+        const double h = phi - a * Q - a * k;
+        const double an = a + h / (Q + k);
+        if (std::fabs(an - a) <= 2e-16 * std::fabs(an)) return an;
+        a = an;
+    }
+    return a;
+}
+
+qp_status check_ws(uint64_t n, const qp_search_cfg_t *cfg, const void *ws, size_t ws_bytes)
+{
+    if (!ws || !aligned16(ws)) return QP_EINVAL;
+    const size_t need = qp_workspace_bytes(n, cfg);
+    if (need == 0) return QP_EINVAL;
+    if (ws_bytes < need) return QP_ENOSPC;
+    return QP_OK;
+}
+
+qp_status check_cfg(const qp_search_cfg_t *cfg)
+{
+    if (!cfg) return QP_OK;
+    if (cfg->t_steps < 1 || cfg->t_steps > kMaxT) return QP_EINVAL;
+    if (cfg->cands_per_round < 1 || cfg->cands_per_round > kMaxCandsPerRound) return QP_EINVAL;
+    if (cfg->dist != QP_LAPLACE) return QP_EINVAL;
+    return QP_OK;
+}
+
+qp_status hip_status(hipError_t e) { return e == hipSuccess ? QP_OK : QP_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t qp_packed_bytes(uint64_t n, uint32_t bits)
+{
+    if (!bits_ok(bits)) return 0;
+    return (size_t)(4u * ((n * (uint64_t)bits + 31u) / 32u));
+}
+
+void qp_default_search_cfg(qp_search_cfg_t *cfg)
+{
+    if (!cfg) return;
+    cfg->t_steps = 100;
+    cfg->cands_per_round = 32;
+    cfg->nbins = 2048;
+    cfg->dist = QP_LAPLACE;
+}
+
+size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg)
+{
+    if (n == 0 || n > kMaxN) return 0;
+    if (check_cfg(cfg) != QP_OK) return 0;
+    const uint32_t t = cfg ? cfg->t_steps : 100u;
+    return kOffSearchPart + (size_t)search_blocks(n) * (t + 1u) * sizeof(double);
+}
+
+size_t qp_ws_offset(qp_ws_region region)
+{
+    switch (region) {
+        case QP_WS_STATS: return kOffStats;
+        case QP_WS_RESULT: return kOffResult;
+        case QP_WS_QPARAMS: return kOffQParams;
+        case QP_WS_HIST: return kOffHist;
+        case QP_WS_CANDS: return kOffCands;
+        case QP_WS_SCORES: return kOffScores;
+        default: return (size_t)-1;
+    }
+}
+
+qp_status qp_stats_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t nbins, void *ws_dev, size_t ws_bytes,
+                         void *stream)
+{
+    if (!x_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || nbins < 16 || nbins > kMaxBins || !aligned16(x_dev))
+        return QP_EINVAL;
+    if (!ws_dev || !aligned16(ws_dev)) return QP_EINVAL;
+    if (ws_bytes < kOffSearchPart) return QP_ENOSPC;   // the statistics use only the fixed-size head
+    return hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream)));
+}
+
+qp_status qp_stats(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t nbins, void *ws_dev, size_t ws_bytes,
+                   void *stream, qp_stats_t *out_host)
+{
+    if (!out_host) return QP_EINVAL;
+    const qp_status st = qp_stats_async(x_dev, n, dtype, nbins, ws_dev, ws_bytes, stream);
+    if (st != QP_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(out_host, static_cast<char *>(ws_dev) + kOffStats, sizeof(qp_stats_t), hipMemcpyDeviceToHost,
+                       s) != hipSuccess)
+        return QP_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return QP_EHIP;
+    return out_host->n_nonfinite ? QP_ENONFINITE : QP_OK;
+}
+
+double qp_aciq_constant(uint32_t bits, qp_dist dist)
+{
+    if (!bits_ok(bits)) return NAN;
+    if (dist == QP_LAPLACE) return laplace_constant(bits);
+    if (dist == QP_GAUSS) return gauss_constant(bits);
+    return NAN;
+}
+
+qp_status qp_aciq_alpha(const qp_stats_t *stats, uint32_t bits, qp_dist dist, double *alpha_out)
+{
+    if (!stats || !alpha_out || !bits_ok(bits)) return QP_EINVAL;
+    if (dist == QP_LAPLACE) *alpha_out = laplace_constant(bits) * stats->mad;
+    else if (dist == QP_GAUSS) *alpha_out = gauss_constant(bits) * std::sqrt(stats->var);
+    else return QP_EINVAL;
+    return QP_OK;
+}
+
+qp_status qp_make_qparams(double center, double alpha, uint32_t bits, uint64_t n, qp_qparams_t *out)
+{
+    if (!out || !bits_ok(bits)) return QP_EINVAL;
+    out->bits = bits;
+    out->reserved = 0;
+    out->n = n;
+    make_grid(center, alpha, bits, out->lo, out->hi, out->scale, out->inv_scale);
+    return QP_OK;
+}
+
+static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats, uint32_t bits,
+                               const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream)
+{
+    if (!x_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || !bits_ok(bits) || !aligned16(x_dev)) return QP_EINVAL;
+    if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
+    const qp_status w = check_ws(n, cfg, ws_dev, ws_bytes);
+    if (w != QP_OK) return w;
+    const uint32_t t = cfg ? cfg->t_steps : 100u;
+    const uint32_t cpr = cfg ? cfg->cands_per_round : 32u;
+    return hip_status(launch_search(x_dev, n, dtype, bits, t, cpr, laplace_constant(bits), stats, ws_dev,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
+                                 const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream)
+{
+    return search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream);
+}
+
+qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats, uint32_t bits,
+                           const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream,
+                           qp_search_result_t *res_host, qp_qparams_t *qparams_out_host)
+{
+    if (!stats) return QP_EINVAL;
+    const qp_status st = search_common(x_dev, n, dtype, stats, bits, cfg, ws_dev, ws_bytes, stream);
+    if (st != QP_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws_dev);
+    if (res_host &&
+        hipMemcpyAsync(res_host, w + kOffResult, sizeof(qp_search_result_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return QP_EHIP;
+    if (qparams_out_host &&
+        hipMemcpyAsync(qparams_out_host, w + kOffQParams, sizeof(qp_qparams_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return QP_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return QP_EHIP;
+    return QP_OK;
+}
+
+static qp_status pack_common(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_qparams_t *hq,
+                             const qp_qparams_t *dq, void *packed_dev, size_t packed_bytes, void *stream)
+{
+    if (!x_dev || !packed_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || !bits_ok(bits) || !aligned16(x_dev) ||
+        !aligned16(packed_dev))
+        return QP_EINVAL;
+    if (packed_bytes < qp_packed_bytes(n, bits)) return QP_ENOSPC;
+    return hip_status(launch_quant_pack(x_dev, n, dtype, bits, hq, dq, packed_dev, static_cast<hipStream_t>(stream)));
+}
+
+qp_status qp_quant_pack(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_qparams_t *qparams, void *packed_dev,
+                        size_t packed_bytes, void *stream)
+{
+    if (!qparams || qparams->n != n) return QP_EINVAL;
+    return pack_common(x_dev, n, dtype, qparams->bits, qparams, nullptr, packed_dev, packed_bytes, stream);
+}
+
+qp_status qp_quant_pack_dev(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
+                            const qp_qparams_t *qparams_dev, void *packed_dev, size_t packed_bytes, void *stream)
+{
+    if (!qparams_dev) return QP_EINVAL;
+    return pack_common(x_dev, n, dtype, bits, nullptr, qparams_dev, packed_dev, packed_bytes, stream);
+}
+
+static qp_status unpack_common(const void *packed_dev, size_t packed_bytes, uint32_t bits, const qp_qparams_t *hq,
+                               const qp_qparams_t *dq, float *y_dev, uint64_t n, void *stream)
+{
+    if (!packed_dev || !y_dev || n == 0 || n > kMaxN || !bits_ok(bits) || !aligned16(packed_dev) || !aligned16(y_dev))
+        return QP_EINVAL;
+    if (packed_bytes < qp_packed_bytes(n, bits)) return QP_ENOSPC;
+    return hip_status(launch_unpack_dequant(packed_dev, bits, hq, dq, y_dev, n, static_cast<hipStream_t>(stream)));
+}
+
+qp_status qp_unpack_dequant(const void *packed_dev, size_t packed_bytes, const qp_qparams_t *qparams, float *y_dev,
+                            uint64_t n, void *stream)
+{
+    if (!qparams || qparams->n != n) return QP_EINVAL;
+    return unpack_common(packed_dev, packed_bytes, qparams->bits, qparams, nullptr, y_dev, n, stream);
+}
+
+qp_status qp_unpack_dequant_dev(const void *packed_dev, size_t packed_bytes, uint32_t bits,
+                                const qp_qparams_t *qparams_dev, float *y_dev, uint64_t n, void *stream)
+{
+    if (!qparams_dev) return QP_EINVAL;
+    return unpack_common(packed_dev, packed_bytes, bits, nullptr, qparams_dev, y_dev, n, stream);
+}
+
+qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_search_cfg_t *cfg,
+                            void *ws_dev, size_t ws_bytes, void *packed_dev, size_t packed_bytes,
+                            qp_qparams_t *qparams_out_dev, void *stream)
+{
+    if (!packed_dev || !bits_ok(bits) || !aligned16(packed_dev)) return QP_EINVAL;
+    if (packed_bytes < qp_packed_bytes(n, bits)) return QP_ENOSPC;
+    const uint32_t nbins = (cfg && cfg->nbins) ? cfg->nbins : 2048u;
+    qp_status st = check_ws(n, cfg, ws_dev, ws_bytes);
+    if (st != QP_OK) return st;
+    st = qp_stats_async(x_dev, n, dtype, nbins, ws_dev, ws_bytes, stream);
+    if (st != QP_OK) return st;
+    st = qp_dsaciq_search_async(x_dev, n, dtype, bits, cfg, ws_dev, ws_bytes, stream);
+    if (st != QP_OK) return st;
+    const qp_qparams_t *qdev = reinterpret_cast<const qp_qparams_t *>(static_cast<char *>(ws_dev) + kOffQParams);
+    st = qp_quant_pack_dev(x_dev, n, dtype, bits, qdev, packed_dev, packed_bytes, stream);
+    if (st != QP_OK) return st;
+    if (qparams_out_dev &&
+        hipMemcpyAsync(qparams_out_dev, qdev, sizeof(qp_qparams_t), hipMemcpyDeviceToDevice,
+                       static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QP_EHIP;
+    return QP_OK;
+}
+
+const char *qp_strerror(qp_status status)
+{
+    switch (status) {
+        case QP_OK: return "ok";
+        case QP_EINVAL: return "invalid argument";
+        case QP_ENOSPC: return "buffer or workspace too small";
+        case QP_EHIP: return "HIP runtime error";
+        case QP_ENONFINITE: return "tensor contains NaN or Inf";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

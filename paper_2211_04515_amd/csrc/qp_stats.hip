@@ -1,0 +1,300 @@
+// Step 1: per-tensor statistics and histogram (Sec. 3: mu and b of L(mu, b); the
+// estimate b_E; the histogram D_R of the real data; the bound b_R from its peak).
+//
+// Two streaming passes, both HBM-bound (4 B per fp32 element each):
+//   pass 1  sum, sum|x|, min, max, NaN/Inf count        -> one partial per block
+//   pass 2  sum|x - mu|, sum (x - mu)^2, histogram      -> partial per block + LDS histogram
+// Accumulation is fp64 per lane, reduced with wave64 shuffles, one LDS slot per wave,
+// then across blocks in index order: no floating-point atomics, so results are
+// bit-reproducible from run to run.  Pass 2 needs mu, min and max; every block of pass 2
+// re-reduces the (at most 1024) pass-1 partials itself, which removes one launch and one
+// grid-wide dependency.  The last block of pass 2 to finish (an integer ticket) reduces
+// the pass-2 partials, finds the histogram peak and writes the qp_stats_t record.
+#include "qp_common.hpp"
+
+namespace qp {
+
+constexpr int kS1Threads = 256;
+constexpr int kS1Unroll = 4;     // 16-byte loads in flight per lane
+constexpr int kS2Threads = 512;
+constexpr int kS2Unroll = 4;
+
+struct Acc1 {
+    double s, sa;
+    float mn, mx;
+    uint32_t bad;
+};
+
+__device__ __forceinline__ void acc1_add(Acc1 &a, float v)
+{
+    const double d = (double)v;
+    a.s += d;
+    a.sa += fabs(d);
+    a.mn = fminf(a.mn, v);
+    a.mx = fmaxf(a.mx, v);
+    a.bad += (__builtin_isfinite(v) ? 0u : 1u);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kS1Threads) void k_stats_pass1(const void *__restrict__ x, uint64_t n,
+                                                            Part1 *__restrict__ part, uint32_t *__restrict__ hist,
+                                                            uint32_t nbins, Ctl *__restrict__ ctl)
+{
+    const uint32_t tid = threadIdx.x;
+    // Clear what pass 2 and the search accumulate into (they run after this kernel on the stream).
+    if (blockIdx.x == 0) {
+        for (uint32_t b = tid; b < nbins; b += kS1Threads) hist[b] = 0u;
+        if (tid == 0) {
+            ctl->ticket_stats2 = 0u;
+            ctl->ticket_search = 0u;
+        }
+    }
+
+    Acc1 a0{0.0, 0.0, INFINITY, -INFINITY, 0u};
+    Acc1 a1 = a0;
+    const uint64_t nvec = n / 4;
+    const uint64_t tile = (uint64_t)kS1Threads * kS1Unroll;
+    uint64_t base = (uint64_t)blockIdx.x * tile;
+    const uint64_t stride = (uint64_t)gridDim.x * tile;
+    for (; base + tile <= nvec; base += stride) {
+        float f[kS1Unroll][4];
+#pragma unroll
+        for (int u = 0; u < kS1Unroll; ++u) Vec4<DT>::load(x, base + (uint64_t)u * kS1Threads + tid, f[u]);
+#pragma unroll
+        for (int u = 0; u < kS1Unroll; ++u) {
+            acc1_add(a0, f[u][0]);
+            acc1_add(a1, f[u][1]);
+            acc1_add(a0, f[u][2]);
+            acc1_add(a1, f[u][3]);
+        }
+    }
+    // the block whose turn it is takes the ragged remainder of whole vectors
+    if (base < nvec) {
+        for (uint64_t v = base + tid; v < nvec; v += kS1Threads) {
+            float f[4];
+            Vec4<DT>::load(x, v, f);
+            acc1_add(a0, f[0]);
+            acc1_add(a1, f[1]);
+            acc1_add(a0, f[2]);
+            acc1_add(a1, f[3]);
+        }
+    }
+    // last n mod 4 elements
+    if (blockIdx.x == 0 && tid < (uint32_t)(n - nvec * 4)) acc1_add(a0, Vec4<DT>::load1(x, nvec * 4 + tid));
+
+    double s = wave_sum(a0.s + a1.s);
+    double sa = wave_sum(a0.sa + a1.sa);
+    float mn = wave_min(fminf(a0.mn, a1.mn));
+    float mx = wave_max(fmaxf(a0.mx, a1.mx));
+    uint32_t bad = wave_sum_u32(a0.bad + a1.bad);
+
+    __shared__ Part1 sh[kS1Threads / kWave];
+    const uint32_t wave = tid / kWave, lane = tid % kWave;
+    if (lane == 0) sh[wave] = Part1{s, sa, mn, mx, bad, 0u};
+    __syncthreads();
+    if (tid == 0) {
+        Part1 p = sh[0];
+        for (int w = 1; w < kS1Threads / kWave; ++w) {
+            p.sum += sh[w].sum;
+            p.sum_abs += sh[w].sum_abs;
+            p.mn = fminf(p.mn, sh[w].mn);
+            p.mx = fmaxf(p.mx, sh[w].mx);
+            p.bad += sh[w].bad;
+        }
+        part[blockIdx.x] = p;
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restrict__ x, uint64_t n,
+                                                            const Part1 *__restrict__ part1, uint32_t nb1,
+                                                            Part2 *__restrict__ part2, uint32_t *__restrict__ hist,
+                                                            uint32_t nbins, Ctl *__restrict__ ctl,
+                                                            qp_stats_t *__restrict__ out)
+{
+    __shared__ uint32_t sh_hist[kMaxBins];
+    __shared__ Part1 sh1[kS2Threads / kWave];
+    __shared__ Part2 sh2[kS2Threads / kWave];
+    __shared__ uint32_t sh_flag;
+    __shared__ uint32_t sh_peak[kS2Threads / kWave];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t wave = tid / kWave, lane = tid % kWave;
+
+    for (uint32_t b = tid; b < nbins; b += kS2Threads) sh_hist[b] = 0u;
+
+    // ---- every block reduces the pass-1 partials in the same fixed order ----
+    Part1 t{0.0, 0.0, INFINITY, -INFINITY, 0u, 0u};
+    for (uint32_t i = tid; i < nb1; i += kS2Threads) {
+        const Part1 p = part1[i];
+        t.sum += p.sum;
+        t.sum_abs += p.sum_abs;
+        t.mn = fminf(t.mn, p.mn);
+        t.mx = fmaxf(t.mx, p.mx);
+        t.bad += p.bad;
+    }
+    t.sum = wave_sum(t.sum);
+    t.sum_abs = wave_sum(t.sum_abs);
+    t.mn = wave_min(t.mn);
+    t.mx = wave_max(t.mx);
+    t.bad = wave_sum_u32(t.bad);
+    if (lane == 0) sh1[wave] = t;
+    __syncthreads();
+    Part1 tot = sh1[0];
+#pragma unroll
+    for (int w = 1; w < kS2Threads / kWave; ++w) {
+        tot.sum += sh1[w].sum;
+        tot.sum_abs += sh1[w].sum_abs;
+        tot.mn = fminf(tot.mn, sh1[w].mn);
+        tot.mx = fmaxf(tot.mx, sh1[w].mx);
+        tot.bad += sh1[w].bad;
+    }
+    const double mean = tot.sum / (double)n;
+    const float mn = tot.mn, mx = tot.mx;
+    // bin index arithmetic in fp32: one subtraction and one division here (the fp64 quotient of
+    // two fp32 values rounded to fp32 equals the correctly rounded fp32 quotient), then one
+    // subtraction and one product per element
+    const float range = mx - mn;
+    const float w_inv = (float)((double)(float)nbins / (double)range);
+    const float top = (float)(nbins - 1u);
+
+    double dev0 = 0.0, dev1 = 0.0, sq0 = 0.0, sq1 = 0.0;
+    auto add = [&](float v, double &dev, double &sq) {
+        const double d = (double)v - mean;
+        dev += fabs(d);
+        sq = fma(d, d, sq);
+        const float tt = (v - mn) * w_inv;
+        const uint32_t idx = (uint32_t)fminf(fmaxf(tt, 0.0f), top);   // NaN (0*inf) -> 0
+        atomicAdd(&sh_hist[idx], 1u);
+    };
+    const uint64_t nvec = n / 4;
+    const uint64_t tile = (uint64_t)kS2Threads * kS2Unroll;
+    uint64_t base = (uint64_t)blockIdx.x * tile;
+    const uint64_t stride = (uint64_t)gridDim.x * tile;
+    for (; base + tile <= nvec; base += stride) {
+        float f[kS2Unroll][4];
+#pragma unroll
+        for (int u = 0; u < kS2Unroll; ++u) Vec4<DT>::load(x, base + (uint64_t)u * kS2Threads + tid, f[u]);
+#pragma unroll
+        for (int u = 0; u < kS2Unroll; ++u) {
+            add(f[u][0], dev0, sq0);
+            add(f[u][1], dev1, sq1);
+            add(f[u][2], dev0, sq0);
+            add(f[u][3], dev1, sq1);
+        }
+    }
+    if (base < nvec) {
+        for (uint64_t v = base + tid; v < nvec; v += kS2Threads) {
+            float f[4];
+            Vec4<DT>::load(x, v, f);
+            add(f[0], dev0, sq0);
+            add(f[1], dev1, sq1);
+            add(f[2], dev0, sq0);
+            add(f[3], dev1, sq1);
+        }
+    }
+    if (blockIdx.x == 0 && tid < (uint32_t)(n - nvec * 4)) add(Vec4<DT>::load1(x, nvec * 4 + tid), dev0, sq0);
+
+    const double dev = wave_sum(dev0 + dev1);
+    const double sq = wave_sum(sq0 + sq1);
+    if (lane == 0) sh2[wave] = Part2{dev, sq};
+    __syncthreads();   // also orders the LDS histogram updates before the merge below
+    for (uint32_t b = tid; b < nbins; b += kS2Threads) {
+        const uint32_t c = sh_hist[b];
+        if (c) atomicAdd(&hist[b], c);
+    }
+    if (tid == 0) {
+        Part2 p = sh2[0];
+        for (int w = 1; w < kS2Threads / kWave; ++w) {
+            p.dev += sh2[w].dev;
+            p.sq += sh2[w].sq;
+        }
+        part2[blockIdx.x] = p;
+    }
+    // ---- ticket: the last block to arrive finishes the job ----
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_stats2, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        sh_flag = (prev == gridDim.x - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!sh_flag) return;
+    __threadfence();
+
+    // pass-2 partials in block order, split over the lanes of the block in a fixed pattern
+    Part2 q{0.0, 0.0};
+    for (uint32_t i = tid; i < gridDim.x; i += kS2Threads) {
+        const Part2 p = part2[i];
+        q.dev += p.dev;
+        q.sq += p.sq;
+    }
+    q.dev = wave_sum(q.dev);
+    q.sq = wave_sum(q.sq);
+    uint32_t peak = 0u;
+    for (uint32_t b = tid; b < nbins; b += kS2Threads)
+        peak = max(peak, __hip_atomic_load(&hist[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    peak = wave_max_u32(peak);
+    __syncthreads();
+    if (lane == 0) {
+        sh2[wave] = q;
+        sh_peak[wave] = peak;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        Part2 p = sh2[0];
+        uint32_t pk = sh_peak[0];
+        for (int w = 1; w < kS2Threads / kWave; ++w) {
+            p.dev += sh2[w].dev;
+            p.sq += sh2[w].sq;
+            pk = max(pk, sh_peak[w]);
+        }
+        qp_stats_t st;
+        st.n = n;
+        st.n_nonfinite = tot.bad;
+        st.mean = mean;
+        st.mad = p.dev / (double)n;
+        st.abs_mean = tot.sum_abs / (double)n;
+        st.var = p.sq / (double)n;
+        st.min = (double)mn;
+        st.max = (double)mx;
+        st.nbins = nbins;
+        st.peak_count = pk;
+        if (mx == mn) {
+            st.peak_density = 0.0;
+            st.b_r = 0.0;
+        } else {
+            const double binw = ((double)mx - (double)mn) / (double)nbins;
+            st.peak_density = (double)pk / ((double)n * binw);
+            st.b_r = 1.0 / (2.0 * st.peak_density);
+        }
+        *out = st;
+        ctl->ticket_stats2 = 0u;
+    }
+}
+
+hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s)
+{
+    char *w = static_cast<char *>(ws);
+    Part1 *p1 = reinterpret_cast<Part1 *>(w + kOffPart1);
+    Part2 *p2 = reinterpret_cast<Part2 *>(w + kOffPart2);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(w + kOffHist);
+    Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
+    qp_stats_t *out = reinterpret_cast<qp_stats_t *>(w + kOffStats);
+    const uint64_t nvec = n / 4;
+    uint32_t nb1 = ceil_div_u64(nvec, (uint64_t)kS1Threads * kS1Unroll);
+    nb1 = nb1 < 1 ? 1 : (nb1 > kMaxStat1Blocks ? kMaxStat1Blocks : nb1);
+    uint32_t nb2 = ceil_div_u64(nvec, (uint64_t)kS2Threads * kS2Unroll);
+    nb2 = nb2 < 1 ? 1 : (nb2 > kMaxStat2Blocks ? kMaxStat2Blocks : nb2);
+    if (dtype == QP_F32) {
+        hipLaunchKernelGGL(k_stats_pass1<QP_F32>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
+        hipLaunchKernelGGL(k_stats_pass2<QP_F32>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins,
+                           ctl, out);
+    } else {
+        hipLaunchKernelGGL(k_stats_pass1<QP_BF16>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
+        hipLaunchKernelGGL(k_stats_pass2<QP_BF16>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins,
+                           ctl, out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace qp

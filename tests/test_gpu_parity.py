@@ -1,0 +1,436 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Needs a real MI355X: run with -m gpu."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import qp_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+BITS = (2, 3, 4, 6, 8, 16)
+
+# Tolerances (floating point): statistics and alpha 1e-5 relative is the stated bar; what the
+# arithmetic gives is far tighter (fp64 sums that differ only in summation order), and the
+# tests hold it to 1e-11 so that a real defect cannot hide inside the bar.
+REL_STATS = 1e-11
+REL_SCORE = 1e-11
+
+
+@pytest.fixture(scope="module")
+def qp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2211_04515_amd as m
+    m.lib()
+    return m
+
+
+def to_dev(x):
+    """numpy float32 array, or uint16 array of bf16 bit patterns -> device tensor."""
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+
+
+def as_f32(x):
+    return orc.widen_bf16(x) if x.dtype == np.uint16 else x
+
+
+def oracle_stats_from(st):
+    o = orc.Stats()
+    for name, _ in orc.Stats._fields_:
+        setattr(o, name, getattr(st, name))
+    return o
+
+
+def oracle_q_from(q):
+    return orc.qparams_from_floats(q.bits, q.n, q.lo, q.hi, q.scale, q.inv_scale)
+
+
+def inputs_small():
+    cases = [("C1", si.make_config("C1")),
+             ("C2_ragged", si.make_config("C2", n=1_234_567)),
+             ("C3_ragged", si.make_config("C3", n=987_653)),
+             ("C4_scaled", (si.make_config("C4", n=300_001) * np.float32(1.7))),
+             ("C5_bf16", si.make_config("C5", n=777_779))]
+    cases += si.edge_cases()
+    return cases
+
+
+SMALL = inputs_small()
+SMALL_IDS = [c[0] for c in SMALL]
+
+
+# ----------------------------------------------------------------------------- step 1
+
+@pytest.mark.parametrize("name,x", SMALL, ids=SMALL_IDS)
+def test_stats_match_oracle(qp, name, x):
+    print(f"[case] stats {name} n={x.size}", flush=True)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    rc, ref, hist_ref = orc.stats(as_f32(x), want_hist=True)
+    assert rc == 0
+    assert st.n == ref.n == x.size and st.n_nonfinite == 0
+    assert st.min == ref.min and st.max == ref.max
+    for f in ("mean", "mad", "abs_mean", "var"):
+        a, b = getattr(st, f), getattr(ref, f)
+        scale = max(abs(b), ref.abs_mean * 1e-3 if f == "mean" else 0.0)
+        assert abs(a - b) <= REL_STATS * scale + 0.0, (f, a, b)
+    off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    hist = ws[off:off + 4 * 2048].cpu().numpy().view(np.uint32)
+    assert np.array_equal(hist, hist_ref[:2048])           # integer work: exact
+    assert st.peak_count == ref.peak_count and st.nbins == 2048
+    assert st.peak_density == pytest.approx(ref.peak_density, rel=1e-14)
+    assert st.b_r == pytest.approx(ref.b_r, rel=1e-14)
+
+
+def test_stats_other_bin_counts(qp):
+    x = si.make_config("C2", n=200_003)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    for nbins in (16, 100, 4096):
+        st = qp.qp_stats(xd, ws, nbins=nbins)
+        rc, ref, hist_ref = orc.stats(x, nbins=nbins, want_hist=True)
+        off = qp.qp_ws_offset(qp.QP_WS_HIST)
+        hist = ws[off:off + 4 * nbins].cpu().numpy().view(np.uint32)
+        assert np.array_equal(hist, hist_ref[:nbins])
+        assert st.peak_count == ref.peak_count and st.b_r == pytest.approx(ref.b_r, rel=1e-14)
+
+
+def test_stats_nonfinite_is_an_error(qp):
+    x = si.make_config("C1").copy()
+    x[5] = np.nan
+    x[77777] = -np.inf
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    with pytest.raises(qp.QuantPipeError) as e:
+        qp.qp_stats(xd, ws)
+    assert e.value.status == qp.QP_ENONFINITE
+    st = qp.qp_stats(xd, ws, allow_nonfinite=True)
+    assert st.n_nonfinite == 2
+
+
+def test_stats_are_bit_reproducible(qp):
+    x = si.make_config("C3", n=2_000_003)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    first = bytes(qp.qp_stats(xd, ws))
+    for _ in range(10):
+        assert bytes(qp.qp_stats(xd, ws)) == first
+
+
+# ----------------------------------------------------------------------------- step 2
+
+def test_aciq_alpha_matches_oracle(qp):
+    x = si.make_config("C1")
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(to_dev(x), ws)
+    ost = oracle_stats_from(st)
+    for bits in BITS:
+        assert qp.qp_aciq_alpha(st, bits) == pytest.approx(orc.aciq_alpha(ost, bits), rel=1e-14)
+        assert qp.qp_aciq_alpha(st, bits, qp.QP_GAUSS) == pytest.approx(orc.aciq_alpha(ost, bits, orc.GAUSS), rel=1e-12)
+
+
+SEARCH_CASES = [("C1", None, (2, 4, 8)), ("C2", 300_007, BITS), ("C3", 250_001, (2, 4, 8)),
+                ("C4", 200_000, (2, 6, 16)), ("C5", 300_011, (2, 3, 4, 8))]
+
+
+@pytest.mark.parametrize("name,n,bitset", SEARCH_CASES, ids=[c[0] for c in SEARCH_CASES])
+def test_search_matches_oracle(qp, name, n, bitset):
+    x = si.make_config(name, n=n)
+    xf = as_f32(x)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    rc, ost_own = orc.stats(xf)
+    for bits in bitset:
+        print(f"[case] search {name} n={x.size} bits={bits}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+        scores = ws[off:off + 8 * 101].cpu().numpy().view(np.float64)
+        # (i) oracle given the GPU's statistics: same grid, so scores differ only by summation order
+        ores, oq, oscores = orc.dsaciq_search(xf, oracle_stats_from(st), bits, 100)
+        assert np.allclose(scores, oscores, rtol=REL_SCORE, atol=0.0)
+        if res.j_star != ores.j_star:   # only an exact numerical tie may differ
+            assert abs(oscores[res.j_star] - oscores[ores.j_star]) <= 1e-12 * oscores[ores.j_star]
+        else:
+            assert res.alpha_star == pytest.approx(ores.alpha_star, rel=1e-14)
+            assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        assert res.mse_star == pytest.approx(ores.mse_star, rel=REL_SCORE)
+        assert res.mse_aciq == pytest.approx(ores.mse_aciq, rel=REL_SCORE)
+        assert res.mse_star <= res.mse_aciq and res.t_steps == 100
+        assert (q.bits, q.n) == (bits, x.size)
+        # (ii) oracle end to end from its own statistics: the stated bar, 1e-5 relative on alpha
+        ores2, _, _ = orc.dsaciq_search(xf, ost_own, bits, 100)
+        if ores2.j_star == res.j_star:
+            assert res.alpha_star == pytest.approx(ores2.alpha_star, rel=1e-5)
+        # the candidate table itself
+        offc = qp.qp_ws_offset(qp.QP_WS_CANDS)
+        cands = ws[offc:offc + 16 * 101].cpu().numpy().view(np.float32).reshape(101, 4)
+        F = orc.laplace_F(bits)
+        for j in (0, 1, 50, 100):
+            b = st.mad + j * ((st.b_r - st.mad) / 100)
+            oqj = orc.make_qparams(st.mean, F * b, bits, x.size)
+            assert tuple(cands[j]) == (oqj.lo, oqj.hi, oqj.scale, oqj.inv_scale)
+
+
+def test_search_result_does_not_depend_on_candidates_per_round(qp):
+    x = si.make_config("C3", n=150_001)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    ref = None
+    for cpr in (32, 1, 7, 16, 25):
+        cfg = qp.qp_default_search_cfg()
+        cfg.cands_per_round = cpr
+        res, q = qp.qp_dsaciq_search(xd, st, 4, ws, cfg=cfg)
+        scores = ws[off:off + 8 * 101].cpu().numpy().view(np.float64).copy()
+        if ref is None:
+            ref = (scores, res.j_star, bytes(q))
+        else:
+            assert np.array_equal(scores, ref[0]) and res.j_star == ref[1] and bytes(q) == ref[2]
+
+
+def test_search_other_step_counts(qp):
+    x = si.make_config("C3", n=60_001)
+    xd = to_dev(x)
+    st = None
+    for t in (1, 10, 333):
+        cfg = qp.qp_default_search_cfg()
+        cfg.t_steps = t
+        ws = qp.alloc_workspace(x.size, cfg)
+        st = qp.qp_stats(xd, ws)
+        res, q = qp.qp_dsaciq_search(xd, st, 2, ws, cfg=cfg)
+        ores, oq, oscores = orc.dsaciq_search(x, oracle_stats_from(st), 2, t)
+        off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+        scores = ws[off:off + 8 * (t + 1)].cpu().numpy().view(np.float64)
+        assert np.allclose(scores, oscores, rtol=REL_SCORE, atol=0.0)
+        assert res.j_star == ores.j_star and res.t_steps == t
+
+
+@pytest.mark.parametrize("name", ["constant", "zeros", "two_point", "laplace_n1", "laplace_n5"])
+def test_search_degenerate_inputs(qp, name):
+    x = dict(si.edge_cases())[name]
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    res, q = qp.qp_dsaciq_search(xd, st, 4, ws)
+    ores, oq, oscores = orc.dsaciq_search(x, oracle_stats_from(st), 4, 100)
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    scores = ws[off:off + 8 * 101].cpu().numpy().view(np.float64)
+    assert np.allclose(scores, oscores, rtol=REL_SCORE, atol=1e-300)
+    assert res.j_star == ores.j_star
+    assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+
+
+def test_search_is_bit_reproducible(qp):
+    x = si.make_config("C2", n=1_000_003)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    first = None
+    for _ in range(5):
+        res, q = qp.qp_dsaciq_search(xd, st, 3, ws)
+        cur = (ws[off:off + 8 * 101].cpu().numpy().tobytes(), bytes(res), bytes(q))
+        first = first or cur
+        assert cur == first
+
+
+# ----------------------------------------------------------------------------- steps 3 and 4
+
+def gpu_alpha_qparams(qp, x, xd, bits, ws):
+    st = qp.qp_stats(xd, ws)
+    alpha = qp.qp_aciq_alpha(st, bits)
+    return qp.qp_make_qparams(st.mean, alpha, bits, x.size), st, alpha
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("name,x", SMALL, ids=SMALL_IDS)
+def test_pack_and_unpack_match_oracle(qp, name, x, bits):
+    print(f"[case] pack/unpack {name} n={x.size} bits={bits}", flush=True)
+    xf = as_f32(x)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    q, st, alpha = gpu_alpha_qparams(qp, x, xd, bits, ws)
+    # the oracle is given the GPU's alpha and builds its own grid from it: must be the same floats
+    oq = orc.make_qparams(st.mean, alpha, bits, x.size)
+    assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+    packed = qp.alloc_packed(x.size, bits)
+    packed.fill_(0xAB)                                   # tail bits must be overwritten with zeros
+    qp.qp_quant_pack(xd, q, packed)
+    codes_ref = orc.quantize(xf, oq)
+    ref = orc.pack(codes_ref, bits)
+    got = packed.cpu().numpy()
+    assert got.size == ref.size == 4 * ((x.size * bits + 31) // 32)
+    assert np.array_equal(got, ref)                      # bit-exact
+    y = torch.full((x.size,), float("nan"), dtype=torch.float32, device="cuda")
+    qp.qp_unpack_dequant(packed, q, y)
+    yref = orc.dequantize(codes_ref, oq)
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), yref.view(np.uint32))   # 0 ulp (bar: 1 ulp)
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_unpack_of_oracle_stream_with_random_codes(qp, bits):
+    rng = np.random.default_rng(bits)
+    for n in (1, 2, 3, 4, 5, 7, 31, 33, 1021, 8191, 8192, 8193, 32768, 32771, 100_003):
+        codes = rng.integers(0, 2 ** bits, size=n, dtype=np.uint32)
+        stream = orc.pack(codes, bits)
+        oq = orc.make_qparams(-0.3, 2.2, bits, n)
+        q = qp.qp_make_qparams(-0.3, 2.2, bits, n)
+        pd = torch.from_numpy(stream).cuda()
+        y = torch.empty(n, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant(pd, q, y)
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(codes, oq)), (bits, n)
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_pack_special_values_and_naive_range(qp, bits):
+    x = si.make_config("C1").copy()
+    x[:6] = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-40]
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    x_fin = x.copy()
+    x_fin[:3] = 0
+    rc, ost = orc.stats(x_fin)
+    for center, alpha in ((ost.mean, orc.aciq_alpha(ost, bits)), ((ost.min + ost.max) / 2, (ost.max - ost.min) / 2)):
+        q = qp.qp_make_qparams(center, alpha, bits, x.size)
+        oq = orc.make_qparams(center, alpha, bits, x.size)
+        packed = qp.alloc_packed(x.size, bits)
+        qp.qp_quant_pack(xd, q, packed)
+        assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(x, oq), bits))
+
+
+@pytest.mark.parametrize("bits", (2, 3, 16))
+def test_pack_degenerate_grid(qp, bits):
+    x = si.make_config("C1")
+    xd = to_dev(x)
+    q = qp.qp_make_qparams(0.5, 0.0, bits, x.size)
+    packed = qp.alloc_packed(x.size, bits)
+    packed.fill_(0xFF)
+    qp.qp_quant_pack(xd, q, packed)
+    assert int(packed.max()) == 0
+    y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    qp.qp_unpack_dequant(packed, q, y)
+    assert bool((y == 0.5).all())
+
+
+def test_device_resident_path_matches_host_path(qp):
+    x = si.make_config("C3", n=500_009)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    for bits in (2, 6):
+        st = qp.qp_stats(xd, ws)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        p_host = qp.alloc_packed(x.size, bits)
+        qp.qp_quant_pack(xd, q, p_host)
+        y_host = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant(p_host, q, y_host)
+        ws2 = qp.alloc_workspace(x.size)
+        ws2.fill_(0x5A)                                  # the workspace needs no initialisation
+        p_dev = qp.alloc_packed(x.size, bits)
+        qrec = torch.zeros(32, dtype=torch.uint8, device="cuda")
+        qp.qp_compress_async(xd, bits, ws2, p_dev, qparams_out_dev_ptr=qrec.data_ptr())
+        y_dev = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant_dev(p_dev, bits, qrec.data_ptr(), y_dev)
+        torch.cuda.synchronize()
+        assert torch.equal(p_host, p_dev) and torch.equal(y_host, y_dev)
+        assert bytes(qrec.cpu().numpy().tobytes()) == bytes(q)
+        assert bytes(qp.read_ws(ws2, qp.QP_WS_STATS, qp.qp_stats_t)) == bytes(st)
+        assert bytes(qp.read_ws(ws2, qp.QP_WS_RESULT, qp.qp_search_result_t)) == bytes(res)
+
+
+def test_runs_on_a_side_stream(qp):
+    x = si.make_config("C2", n=400_001)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        st = qp.qp_stats(xd, ws)
+        res, q = qp.qp_dsaciq_search(xd, st, 4, ws)
+        packed = qp.alloc_packed(x.size, 4)
+        qp.qp_quant_pack(xd, q, packed)
+    s.synchronize()
+    oq = oracle_q_from(q)
+    assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(x, oq), 4))
+
+
+# ----------------------------------------------------------------------------- full sizes
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+def test_full_size_fp32_configs(qp, name):
+    x = si.make_config(name)
+    if name == "C4":
+        x = x * np.float32(si.c4_stream(1)[0][1])
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    rc, ost, hist_ref = orc.stats(x, want_hist=True)
+    for f in ("mean", "mad", "abs_mean", "var"):
+        assert abs(getattr(st, f) - getattr(ost, f)) <= REL_STATS * max(abs(getattr(ost, f)), 1e-3 * ost.abs_mean)
+    assert (st.min, st.max, st.peak_count) == (ost.min, ost.max, ost.peak_count)
+    off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    assert np.array_equal(ws[off:off + 8192].cpu().numpy().view(np.uint32), hist_ref[:2048])
+    offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for i, bits in enumerate(si.CONFIG_BITS[name]):
+        print(f"[case] full {name} bits={bits}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        scores = ws[offs:offs + 8 * 101].cpu().numpy().view(np.float64).copy()
+        F = orc.laplace_F(bits)
+        if i == 0:   # one whole oracle search per config; the other bitwidths check sampled candidates
+            ores, oq_s, oscores = orc.dsaciq_search(x, oracle_stats_from(st), bits, 100)
+            assert np.allclose(scores, oscores, rtol=REL_SCORE, atol=0.0)
+            assert res.j_star == ores.j_star
+        for j in sorted({0, 100, int(res.j_star)}):
+            b = st.mad + j * ((st.b_r - st.mad) / 100)
+            assert scores[j] == pytest.approx(orc.sq_error(x, orc.make_qparams(st.mean, F * b, bits, x.size)), rel=REL_SCORE)
+        assert res.j_star == int(np.argmin(scores))
+        oq = orc.make_qparams(st.mean, res.alpha_star, bits, x.size)   # oracle given the GPU's alpha
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        packed = qp.alloc_packed(x.size, bits)
+        qp.qp_quant_pack(xd, q, packed)
+        codes = orc.quantize(x, oq)
+        assert np.array_equal(packed.cpu().numpy(), orc.pack(codes, bits))
+        y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant(packed, q, y)
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(codes, oq))
+
+
+@pytest.mark.timeout(1200)
+def test_full_size_bf16_config(qp):
+    h = si.make_config("C5")
+    x = orc.widen_bf16(h)
+    xd = to_dev(h)
+    ws = qp.alloc_workspace(h.size)
+    st = qp.qp_stats(xd, ws)
+    rc, ost, hist_ref = orc.stats(x, want_hist=True)
+    for f in ("mean", "mad", "abs_mean", "var"):
+        assert abs(getattr(st, f) - getattr(ost, f)) <= REL_STATS * max(abs(getattr(ost, f)), 1e-3 * ost.abs_mean)
+    assert (st.min, st.max, st.peak_count) == (ost.min, ost.max, ost.peak_count)
+    offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for bits in si.CONFIG_BITS["C5"]:
+        print(f"[case] full C5 bits={bits}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        scores = ws[offs:offs + 8 * 101].cpu().numpy().view(np.float64).copy()
+        F = orc.laplace_F(bits)
+        for j in sorted({0, int(res.j_star)}):      # sampled candidates: the oracle scores them one by one
+            b = st.mad + j * ((st.b_r - st.mad) / 100)
+            assert scores[j] == pytest.approx(orc.sq_error(x, orc.make_qparams(st.mean, F * b, bits, x.size)), rel=REL_SCORE)
+        assert res.j_star == int(np.argmin(scores))
+        oq = orc.make_qparams(st.mean, res.alpha_star, bits, x.size)
+        packed = qp.alloc_packed(x.size, bits)
+        qp.qp_quant_pack(xd, q, packed)
+        codes = orc.quantize(x, oq)
+        assert np.array_equal(packed.cpu().numpy(), orc.pack(codes, bits))
+        y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant(packed, q, y)
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(codes, oq))
+        del packed, y, codes

@@ -1,0 +1,181 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+rejects bad arguments before touching the GPU, and its host-only functions agree with the
+oracle.  No kernel is launched here."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import qp_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BITS = (2, 3, 4, 6, 8, 16)
+
+
+@pytest.fixture(scope="module")
+def qp():
+    import paper_2211_04515_amd as m
+    m.lib()
+    return m
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "quantpipe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(qp):
+    names = declared_functions()
+    assert len(names) >= 17 and "qp_stats" in names and "qp_unpack_dequant" in names
+    raw = C.CDLL(os.path.join(ROOT, "paper_2211_04515_amd", "libquantpipe.so"))
+    for n in names:
+        assert hasattr(raw, n), f"{n} declared in quantpipe.h but not exported"
+    from paper_2211_04515_amd import binding
+    assert sorted(binding.EXPORTS) == names          # the Python binding wraps all of them, same names
+    for n in names:
+        assert callable(getattr(qp, n))
+
+
+def test_struct_sizes_match_the_header_layout(qp):
+    assert C.sizeof(qp.qp_stats_t) == 88
+    assert C.sizeof(qp.qp_qparams_t) == 32
+    assert C.sizeof(qp.qp_search_cfg_t) == 16
+    assert C.sizeof(qp.qp_search_result_t) == 56
+    offs = [qp.qp_ws_offset(r) for r in range(6)]
+    assert offs == sorted(offs) and len(set(offs)) == 6 and all(o % 16 == 0 for o in offs)
+    assert qp.qp_ws_offset(99) == 2 ** 64 - 1
+
+
+def test_packed_bytes(qp):
+    for bits in BITS:
+        for n in (0, 1, 31, 32, 33, 1000, 9_682_944, 151_257_088, 2 ** 32 - 1):
+            assert qp.qp_packed_bytes(n, bits) == 4 * ((n * bits + 31) // 32) == orc.packed_bytes(n, bits)
+    for bad in (0, 1, 5, 7, 9, 12, 32):
+        assert qp.qp_packed_bytes(100, bad) == 0
+
+
+def test_workspace_bytes(qp):
+    cfg = qp.qp_default_search_cfg()
+    assert (cfg.t_steps, cfg.cands_per_round, cfg.nbins, cfg.dist) == (100, 32, 2048, qp.QP_LAPLACE)
+    a = qp.qp_workspace_bytes(9_682_944)
+    assert a == qp.qp_workspace_bytes(9_682_944, cfg) and a > qp.qp_ws_offset(qp.QP_WS_SCORES)
+    cfg.t_steps = 1000
+    assert qp.qp_workspace_bytes(9_682_944, cfg) > a
+    assert qp.qp_workspace_bytes(0) == 0 and qp.qp_workspace_bytes(2 ** 32) == 0
+    for t, cpr in ((0, 32), (1024, 32), (100, 0), (100, 33)):
+        cfg = qp.qp_default_search_cfg()
+        cfg.t_steps, cfg.cands_per_round = t, cpr
+        assert qp.qp_workspace_bytes(1000, cfg) == 0
+
+
+def test_aciq_constants_against_scipy_and_oracle(qp):
+    for bits in BITS:
+        F = qp.qp_aciq_constant(bits, qp.QP_LAPLACE)
+        assert F == pytest.approx(scipy.special.lambertw(3 * 4.0 ** bits).real, rel=1e-14)
+        assert F == pytest.approx(orc.laplace_F(bits), rel=1e-14)
+        assert qp.qp_aciq_constant(bits, qp.QP_GAUSS) == pytest.approx(orc.gauss_G(bits), rel=1e-12)
+    assert math.isnan(qp.qp_aciq_constant(5, 0)) and math.isnan(qp.qp_aciq_constant(4, 7))
+
+
+def test_aciq_alpha_host(qp):
+    st = qp.qp_stats_t()
+    st.mad, st.var = 0.37, 0.49
+    for bits in BITS:
+        assert qp.qp_aciq_alpha(st, bits) == pytest.approx(orc.laplace_F(bits) * 0.37, rel=1e-14)
+        assert qp.qp_aciq_alpha(st, bits, qp.QP_GAUSS) == pytest.approx(orc.gauss_G(bits) * 0.7, rel=1e-12)
+    with pytest.raises(qp.QuantPipeError):
+        qp.qp_aciq_alpha(st, 5)
+    with pytest.raises(qp.QuantPipeError):
+        qp.qp_aciq_alpha(st, 4, 3)
+
+
+def test_make_qparams_is_bit_identical_to_the_oracle(qp):
+    rng = np.random.default_rng(0)
+    for _ in range(3000):
+        center = rng.normal(0, 1) * 10.0 ** rng.integers(-6, 6)
+        alpha = abs(rng.normal(0, 1)) * 10.0 ** rng.integers(-8, 8)
+        bits = int(rng.choice(BITS))
+        a = qp.qp_make_qparams(center, alpha, bits, 77)
+        b = orc.make_qparams(center, alpha, bits, 77)
+        assert (a.lo, a.hi, a.scale, a.inv_scale, a.bits, a.n) == (b.lo, b.hi, b.scale, b.inv_scale, bits, 77)
+        assert a.reserved == 0
+    z = qp.qp_make_qparams(3.0, 0.0, 4, 1)
+    assert (z.lo, z.hi, z.scale, z.inv_scale) == (3.0, 3.0, 0.0, 0.0)
+    with pytest.raises(qp.QuantPipeError):
+        qp.qp_make_qparams(0.0, 1.0, 7, 1)
+
+
+def test_argument_errors_are_reported_before_any_gpu_work(qp):
+    L = qp.lib()
+    fake = C.c_void_p(0x10000)          # aligned, never dereferenced on these paths
+    odd = C.c_void_p(0x10004)           # misaligned
+    q = qp.qp_make_qparams(0.0, 1.0, 4, 1000)
+    st = qp.qp_stats_t()
+    big = 1 << 30
+    # null pointers / n == 0 / bad dtype / bad nbins / misalignment
+    assert L.qp_stats(None, 1000, 0, 2048, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 0, 0, 2048, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 1000, 2, 2048, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 1000, 0, 8, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 1000, 0, 5000, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(odd, 1000, 0, 2048, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 1000, 0, 2048, None, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 1000, 0, 2048, fake, big, None, None) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 2 ** 32, 0, 2048, fake, big, None, C.byref(st)) == qp.QP_EINVAL
+    assert L.qp_stats(fake, 1000, 0, 2048, fake, 100, None, C.byref(st)) == qp.QP_ENOSPC
+    # search
+    res, qo = qp.qp_search_result_t(), qp.qp_qparams_t()
+    assert L.qp_dsaciq_search(fake, 1000, 0, None, 4, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
+    assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 5, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
+    assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, None, fake, 1000, None, C.byref(res), C.byref(qo)) == qp.QP_ENOSPC
+    cfg = qp.qp_default_search_cfg()
+    cfg.dist = qp.QP_GAUSS
+    assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
+    cfg = qp.qp_default_search_cfg()
+    cfg.t_steps = 5000
+    assert L.qp_dsaciq_search_async(fake, 1000, 0, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
+    # pack
+    assert L.qp_quant_pack(fake, 1000, 0, None, fake, big, None) == qp.QP_EINVAL
+    assert L.qp_quant_pack(fake, 999, 0, C.byref(q), fake, big, None) == qp.QP_EINVAL        # n mismatch
+    assert L.qp_quant_pack(fake, 1000, 0, C.byref(q), fake, 499, None) == qp.QP_ENOSPC
+    assert L.qp_quant_pack(fake, 1000, 0, C.byref(q), odd, big, None) == qp.QP_EINVAL
+    assert L.qp_quant_pack(None, 1000, 0, C.byref(q), fake, big, None) == qp.QP_EINVAL
+    bad = qp.qp_make_qparams(0.0, 1.0, 4, 1000)
+    bad.bits = 5
+    assert L.qp_quant_pack(fake, 1000, 0, C.byref(bad), fake, big, None) == qp.QP_EINVAL
+    assert L.qp_quant_pack_dev(fake, 1000, 0, 4, None, fake, big, None) == qp.QP_EINVAL
+    # unpack
+    assert L.qp_unpack_dequant(fake, big, None, fake, 1000, None) == qp.QP_EINVAL
+    assert L.qp_unpack_dequant(fake, big, C.byref(q), fake, 1001, None) == qp.QP_EINVAL
+    assert L.qp_unpack_dequant(fake, 499, C.byref(q), fake, 1000, None) == qp.QP_ENOSPC
+    assert L.qp_unpack_dequant(fake, big, C.byref(bad), fake, 1000, None) == qp.QP_EINVAL
+    assert L.qp_unpack_dequant(fake, big, C.byref(q), None, 1000, None) == qp.QP_EINVAL
+    assert L.qp_unpack_dequant_dev(fake, big, 4, None, fake, 1000, None) == qp.QP_EINVAL
+    # whole sender side
+    assert L.qp_compress_async(fake, 1000, 0, 4, None, fake, big, fake, 499, None, None) == qp.QP_ENOSPC
+    assert L.qp_compress_async(fake, 1000, 0, 9, None, fake, big, fake, big, None, None) == qp.QP_EINVAL
+    assert L.qp_compress_async(fake, 1000, 0, 4, None, fake, 64, fake, big, None, None) == qp.QP_ENOSPC
+
+
+def test_strerror(qp):
+    msgs = {qp.qp_strerror(s) for s in (0, -1, -2, -3, -4, -99)}
+    assert len(msgs) == 6 and qp.qp_strerror(0) == "ok"
+
+
+def test_product_package_does_not_reach_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2211_04515_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "qp_oracle" not in text and "import oracle" not in text and "from oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            assert "paper_2211_04515_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f
