@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the activation-compression hot path on one MI355X.
+
+A step is one pass of the whole path (statistics -> DS-ACIQ directed search -> clip +
+quantize + pack -> unpack + dequantize) over the ViT-Base stage-boundary tensor
+64x197x768 fp32, once per bitwidth in {2,3,4,6,8,16} (six passes), with every result kept
+on the device (no host round trip inside the step).  Inputs are synthetic (seeded mixture of
+Laplace and Gaussian values with scaled outliers), resident in HBM before the timed region;
+passes rotate over 16 distinct input/output buffer sets (> 600 MB) so that the tensor is not
+served from the 256 MB Infinity Cache left warm by the previous pass.
+
+Prints ONE JSON line.  `value` is activation bytes entering the path per second.
+`roofline` describes the kernel that dominates the step (the directed-search kernel, bound by
+plain vector ALU work); `roofline_pack` / `roofline_unpack` / `roofline_stats` describe the
+HBM-bound kernels.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
+workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                  # MI355X HBM3E, published
+VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz: one vector op per lane per clock
+SEARCH_LANEOPS_PER_ELEM_CAND = 8       # algorithmic vector operations per element and candidate
+NBUF = 16
+
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
+# None where no counter run has been committed for that kernel yet.
+TRAFFIC_BYTES = {"search": None, "pack": None, "unpack": None, "stats": None}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-reps", type=int, default=64, help="back-to-back launches per kernel timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (tensors shard by microbatch with no exchange); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2211_04515_amd as qp
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    qp.lib()
+    torch.cuda.set_device(0)
+    name = "C2"
+    bits_set = si.CONFIG_BITS[name]
+    x_host = si.make_config(name)
+    n = x_host.size
+    in_bytes = n * 4
+
+    xs = [torch.from_numpy(x_host).cuda() for _ in range(NBUF)]
+    ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(NBUF)]
+    packs = {b: [qp.alloc_packed(n, b) for _ in range(NBUF)] for b in bits_set}
+    ws = qp.alloc_workspace(n)
+    qdev = ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    counter = [0]
+
+    def one_pass(bits, timers=None):
+        i = counter[0] % NBUF
+        counter[0] += 1
+        if timers is None:
+            qp.qp_compress_async(xs[i], bits, ws, packs[bits][i])
+            qp.qp_unpack_dequant_dev(packs[bits][i], bits, qdev, ys[i])
+            return
+        e = [ev() for _ in range(5)]
+        e[0].record()
+        qp.qp_stats_async(xs[i], ws)
+        e[1].record()
+        qp.qp_dsaciq_search_async(xs[i], bits, ws)
+        e[2].record()
+        qp.qp_quant_pack_dev(xs[i], bits, qdev, packs[bits][i])
+        e[3].record()
+        qp.qp_unpack_dequant_dev(packs[bits][i], bits, qdev, ys[i])
+        e[4].record()
+        timers.append((bits, e))
+
+    def step(timers=None):
+        for b in bits_set:
+            one_pass(b, timers)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    timers = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timers)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = len(bits_set) * in_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # stage durations from the HIP events recorded inside the timed region (current stream)
+    stage = {"stats": [], "search": [], "pack": [], "unpack": []}
+    for bits, e in timers:
+        for k, s in enumerate(("stats", "search", "pack", "unpack")):
+            stage[s].append(e[k].elapsed_time(e[k + 1]) * 1e3)
+    mean = lambda v: float(sum(v) / len(v))
+    search_us = mean(stage["search"])       # setup kernel (a few microseconds) + search kernel
+    search_ops = SEARCH_LANEOPS_PER_ELEM_CAND * 101 * n
+    roofline = {"kernel": "k_search_mse<fp32> (+ k_search_setup)", "bound": "alu",
+                "achieved": search_ops / (search_us * 1e-6) / 1e12, "peak": VALU_PEAK_TLANEOPS,
+                "unit": "Tlaneop/s", "frac": None, "traffic": TRAFFIC_BYTES["search"],
+                "us_per_launch": search_us, "timed": "HIP events around every launch inside the timed region"}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+
+    # the HBM-bound kernels: short (about 10 us), so an event pair per launch would add a fifth to
+    # them; time kernel_reps back-to-back launches over rotating buffers between two events
+    def timed_reps(fn):
+        R = args.kernel_reps
+        for r in range(4):
+            fn(r)
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for r in range(R):
+            fn(r)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / R
+
+    per_bits = {}
+    for b in bits_set:
+        q = qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)
+        q = qp.qp_make_qparams((q.lo + q.hi) / 2, (q.hi - q.lo) / 2, b, n)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % NBUF], q, packs[b][r % NBUF]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[b][r % NBUF], q, ys[r % NBUF]))
+        byts = in_bytes + n * b / 8
+        per_bits[str(b)] = {"pack_us": tp, "pack_GBs": byts / tp / 1e3, "unpack_us": tu, "unpack_GBs": byts / tu / 1e3}
+    ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % NBUF], ws))
+
+    def hbm(kernel, byts, us, key):
+        a = byts / us / 1e3
+        return {"kernel": kernel, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": a / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES[key], "us_per_launch": us,
+                "timed": f"{args.kernel_reps} back-to-back launches over {NBUF} rotating buffer sets between two HIP events"}
+
+    # headline for pack / unpack: the mean over the six bitwidths of the workload
+    pack_bytes = sum(in_bytes + n * b / 8 for b in bits_set)
+    pack_us = sum(per_bits[str(b)]["pack_us"] for b in bits_set)
+    unpack_us = sum(per_bits[str(b)]["unpack_us"] for b in bits_set)
+    r_pack = hbm("k_quant_pack<k,fp32>, k in {2,3,4,6,8,16}", pack_bytes / len(bits_set), pack_us / len(bits_set), "pack")
+    r_unpack = hbm("k_unpack_dequant<k>, k in {2,3,4,6,8,16}", pack_bytes / len(bits_set), unpack_us / len(bits_set), "unpack")
+    r_stats = hbm("k_stats_pass1 + k_stats_pass2", 2 * in_bytes, ts, "stats")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(x_host, bits_set)
+
+    out = {
+        "metric": "activation GB/s quantize+pack & unpack+dequant (% HBM peak); DS-ACIQ us/tensor",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C2: ViT-Base stage boundary 64x197x768 fp32, 70% Laplace(0,0.4)/30% N(0.1,1) + 0.05% outliers x30, "
+                               "full path (stats, DS-ACIQ t=100, pack, unpack) once per bitwidth in {2,3,4,6,8,16}",
+                   "elements": n, "bitwidths": list(bits_set), "passes_per_step": len(bits_set), "buffers_rotated": NBUF},
+        "stage_us_in_timed_region": {k: mean(v) for k, v in stage.items()},
+        "dsaciq_us_per_tensor": search_us,
+        "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
+        "per_bitwidth": per_bits,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(x_host, bits_set):
+    """The oracle as it stands (single thread, never tuned), on the first quarter of the tensor."""
+    from oracle import qp_oracle as orc
+    sample = x_host[: x_host.size // 4]
+    t0 = time.perf_counter()
+    rc, st = orc.stats(sample)
+    for b in bits_set:
+        res, q, _ = orc.dsaciq_search(sample, st, b, 100)
+        codes = orc.quantize(sample, q)
+        stream = orc.pack(codes, b)
+        y = orc.dequantize(orc.unpack(stream, sample.size, b), q)
+    dt = time.perf_counter() - t0
+    return {"value": len(bits_set) * sample.size * 4 / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first quarter of the tensor ({sample.size} elements), all six bitwidths, {dt:.1f} s of CPU time",
+            "seconds": dt}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -132,7 +132,8 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     }
 
     // ---- ticket: the last block of the whole grid finishes ----
-    __threadfence();
+    // (the barrier orders all lanes' writes before lane 0's device-scope release and lane 0's
+    // acquire before all lanes' reads: one fencing lane per block, not one per wave)
     __syncthreads();
     if (tid == 0) {
         const uint32_t total = gridDim.x * gridDim.y;
@@ -141,7 +142,6 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     }
     __syncthreads();
     if (!sh_flag) return;
-    __threadfence();
 
     for (uint32_t j = tid; j < ncand; j += kSrThreads) {
         double s = 0.0;

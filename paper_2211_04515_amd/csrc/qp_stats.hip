@@ -211,7 +211,9 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
         part2[blockIdx.x] = p;
     }
     // ---- ticket: the last block to arrive finishes the job ----
-    __threadfence();
+    // The barrier orders every lane's global writes before lane 0's device-scope release, and
+    // lane 0's acquire before every lane's reads below; one lane fences instead of all of them
+    // (a device-scope release writes this XCD's L2 back, which is far too dear to do per wave).
     __syncthreads();
     if (tid == 0) {
         const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_stats2, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
@@ -219,7 +221,6 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
     }
     __syncthreads();
     if (!sh_flag) return;
-    __threadfence();
 
     // pass-2 partials in block order, split over the lanes of the block in a fixed pattern
     Part2 q{0.0, 0.0};
