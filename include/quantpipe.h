@@ -87,7 +87,9 @@ typedef struct {
 /* Directed-search configuration.  The paper sets t_steps = 100 (Sec. 3). */
 typedef struct {
     uint32_t t_steps;          /* 1..1023: candidates j = 0..t_steps */
-    uint32_t cands_per_round;  /* 1..32: candidates scored per pass over the tensor; never changes results */
+    uint32_t cands_per_round;  /* 1..32: most candidates scored per pass over the tensor (small tensors use
+                                  fewer); never changes results.  Default 13: eight even rounds of the 101
+                                  candidates, which is what the gfx950 register file likes best */
     uint32_t nbins;            /* kept with the configuration for callers; the search itself does not use it */
     uint32_t dist;             /* must be QP_LAPLACE (the paper's model) */
 } qp_search_cfg_t;
@@ -118,13 +120,13 @@ typedef enum {
 size_t qp_packed_bytes(uint64_t n, uint32_t bits);
 
 /* Bytes of device workspace needed by qp_stats / qp_dsaciq_search for an n-element
- * tensor under cfg (NULL = defaults: t_steps 100, cands_per_round 32).  0 on bad arguments. */
+ * tensor under cfg (NULL = defaults: t_steps 100, cands_per_round 13).  0 on bad arguments. */
 size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg);
 
 /* Byte offset of a region inside the workspace; (size_t)-1 for an unknown region. */
 size_t qp_ws_offset(qp_ws_region region);
 
-/* Fills cfg with the defaults {100, 32, 2048, QP_LAPLACE}. */
+/* Fills cfg with the defaults {100, 13, 2048, QP_LAPLACE}. */
 void qp_default_search_cfg(qp_search_cfg_t *cfg);
 
 /* ---- step 1: statistics (Sec. 3: mu and b of L(mu, b); b_E; histogram D_R; b_R) ----

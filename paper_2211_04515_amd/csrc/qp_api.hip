@@ -85,7 +85,7 @@ void qp_default_search_cfg(qp_search_cfg_t *cfg)
 {
     if (!cfg) return;
     cfg->t_steps = 100;
-    cfg->cands_per_round = 32;
+    cfg->cands_per_round = 13;
     cfg->nbins = 2048;
     cfg->dist = QP_LAPLACE;
 }
@@ -170,7 +170,7 @@ static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, co
     const qp_status w = check_ws(n, cfg, ws_dev, ws_bytes);
     if (w != QP_OK) return w;
     const uint32_t t = cfg ? cfg->t_steps : 100u;
-    const uint32_t cpr = cfg ? cfg->cands_per_round : 32u;
+    const uint32_t cpr = cfg ? cfg->cands_per_round : 13u;
     return hip_status(launch_search(x_dev, n, dtype, bits, t, cpr, laplace_constant(bits), stats, ws_dev,
                                     static_cast<hipStream_t>(stream)));
 }

@@ -44,7 +44,8 @@ static_assert(sizeof(Cand) == 16, "Cand layout");
 struct Ctl {
     uint32_t ticket_stats2;   // blocks of the second statistics pass that have finished
     uint32_t ticket_search;   // blocks of the search kernel that have finished
-    uint32_t pad0, pad1;
+    uint32_t short_seq;       // 1: the search may drop the clamp of the rounded level
+    uint32_t pad1;
     double b_e, b_r, step, F; // search grid: b_j = b_e + j*step, alpha_j = F*b_j
     double mean;
     uint32_t bits, t_steps;
@@ -59,20 +60,33 @@ constexpr size_t kOffCtl = 256;                                   // Ctl
 constexpr size_t kOffHist = 512;                                  // uint32_t[kMaxBins]
 constexpr size_t kOffCands = kOffHist + kMaxBins * 4;             // Cand[kMaxT + 1]
 constexpr size_t kOffScores = kOffCands + (kMaxT + 1) * sizeof(Cand);   // double[kMaxT + 1]
-constexpr size_t kOffPart1 = kOffScores + (kMaxT + 1) * 8;        // Part1[kMaxStat1Blocks]
+constexpr size_t kOffRoundTickets = kOffScores + (kMaxT + 1) * 8; // uint32_t[kMaxT + 1]: per-round block counters
+constexpr size_t kOffPart1 = kOffRoundTickets + (kMaxT + 1) * 4;  // Part1[kMaxStat1Blocks]
 constexpr size_t kOffPart2 = kOffPart1 + kMaxStat1Blocks * sizeof(Part1);  // Part2[kMaxStat2Blocks]
-constexpr size_t kOffSearchPart = kOffPart2 + kMaxStat2Blocks * sizeof(Part2);  // double[blocks][t + 1]
+constexpr size_t kOffSearchPart = kOffPart2 + kMaxStat2Blocks * sizeof(Part2);  // double[t + 1][blocks]
 static_assert(sizeof(qp_stats_t) <= 128 && sizeof(qp_search_result_t) <= 64 && sizeof(qp_qparams_t) == 32 &&
               sizeof(Ctl) <= 256, "fixed workspace regions");
 static_assert(kOffSearchPart % 16 == 0, "alignment");
 
+// native vector types (the nontemporal builtins want them)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 // ---- element loads: four consecutive elements, widened to fp32 ----------------------
 // fp32: one 16-byte load; bf16: one 8-byte load, the 16 bits become the top half.
+// load_stream is for data touched once (quantize+pack): a nontemporal load keeps it from
+// displacing what other kernels left in L2 / Infinity Cache and measurably raises HBM rate.
 template <int DT> struct Vec4;
 template <> struct Vec4<QP_F32> {
     static __device__ __forceinline__ void load(const void *base, uint64_t vec, float (&f)[4])
     {
         const float4 v = reinterpret_cast<const float4 *>(base)[vec];
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    static __device__ __forceinline__ void load_stream(const void *base, uint64_t vec, float (&f)[4])
+    {
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(base) + vec);
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
     }
     static __device__ __forceinline__ float load1(const void *base, uint64_t i)
@@ -89,42 +103,113 @@ template <> struct Vec4<QP_BF16> {
         f[2] = __uint_as_float(v.y << 16);
         f[3] = __uint_as_float(v.y & 0xffff0000u);
     }
+    static __device__ __forceinline__ void load_stream(const void *base, uint64_t vec, float (&f)[4])
+    {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(base) + vec);
+        f[0] = __uint_as_float(v.x << 16);
+        f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16);
+        f[3] = __uint_as_float(v.y & 0xffff0000u);
+    }
     static __device__ __forceinline__ float load1(const void *base, uint64_t i)
     {
         return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t *>(base)[i]) << 16);
     }
 };
 
-// ---- wave64 reductions (shuffles), then one LDS slot per wave -------------------------
+// ---- "last block finishes" tickets ---------------------------------------------------
+// A block publishes its partial results with a device-scope RELEASE on the ticket counter; only
+// the block that draws the last ticket pays for the ACQUIRE (cache invalidation) before it
+// reads the others' partials.  An acquire in every block would invalidate the XCD's L2 under
+// the blocks still streaming the tensor.
+#ifndef QP_TICKET_MODE
+#define QP_TICKET_MODE 1
+#endif
+#if QP_TICKET_MODE == 0
+#define QP_TICKET_ORDER __ATOMIC_ACQ_REL
+#define QP_TICKET_ACQUIRE() ((void)0)
+#elif QP_TICKET_MODE == 1
+#define QP_TICKET_ORDER __ATOMIC_RELEASE
+#define QP_TICKET_ACQUIRE() __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent")
+#else   // timing probe only: no ordering at all, results are not valid
+#define QP_TICKET_ORDER __ATOMIC_RELAXED
+#define QP_TICKET_ACQUIRE() ((void)0)
+#endif
+
+// ---- wave64 reductions -------------------------------------------------------------------
+// Four DPP steps (lane permutations inside a row of 16 lanes, executed in the vector ALU, no
+// LDS traffic) leave each row's result in all of its lanes; the four rows are then read with
+// v_readlane and combined in a fixed order.  All 64 lanes must be active.  The result is
+// wave-uniform and the order of operations is fixed, so results are bit-reproducible.
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;    // lane i <-> 7-i inside each group of 8
+constexpr int kDppRowMirror = 0x140;     // lane i <-> 15-i inside each row of 16
+
+template <int CTRL> __device__ __forceinline__ int dpp_i32(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(dpp_i32<CTRL>(__float_as_int(v)));
+}
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v)
+{
+    return __hiloint2double(dpp_i32<CTRL>(__double2hiint(v)), dpp_i32<CTRL>(__double2loint(v)));
+}
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    v += dpp_f64<kDppQuadSwap1>(v);
+    v += dpp_f64<kDppQuadSwap2>(v);
+    v += dpp_f64<kDppHalfMirror>(v);
+    v += dpp_f64<kDppRowMirror>(v);
+    return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
 }
 __device__ __forceinline__ float wave_min(float v)
 {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = fminf(v, dpp_f32<kDppQuadSwap1>(v));
+    v = fminf(v, dpp_f32<kDppQuadSwap2>(v));
+    v = fminf(v, dpp_f32<kDppHalfMirror>(v));
+    v = fminf(v, dpp_f32<kDppRowMirror>(v));
+    const int b = __float_as_int(v);
+    return fminf(fminf(__int_as_float(__builtin_amdgcn_readlane(b, 0)), __int_as_float(__builtin_amdgcn_readlane(b, 16))),
+                 fminf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
 }
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = fmaxf(v, dpp_f32<kDppQuadSwap1>(v));
+    v = fmaxf(v, dpp_f32<kDppQuadSwap2>(v));
+    v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+    const int b = __float_as_int(v);
+    return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 0)), __int_as_float(__builtin_amdgcn_readlane(b, 16))),
+                 fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
 }
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    int x = (int)v;
+    x += dpp_i32<kDppQuadSwap1>(x);
+    x += dpp_i32<kDppQuadSwap2>(x);
+    x += dpp_i32<kDppHalfMirror>(x);
+    x += dpp_i32<kDppRowMirror>(x);
+    return (uint32_t)(__builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
+                      __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48));
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor(v, o, kWave));
-    return v;
+    v = max(v, (uint32_t)dpp_i32<kDppQuadSwap1>((int)v));
+    v = max(v, (uint32_t)dpp_i32<kDppQuadSwap2>((int)v));
+    v = max(v, (uint32_t)dpp_i32<kDppHalfMirror>((int)v));
+    v = max(v, (uint32_t)dpp_i32<kDppRowMirror>((int)v));
+    const int b = (int)v;
+    return max(max((uint32_t)__builtin_amdgcn_readlane(b, 0), (uint32_t)__builtin_amdgcn_readlane(b, 16)),
+               max((uint32_t)__builtin_amdgcn_readlane(b, 32), (uint32_t)__builtin_amdgcn_readlane(b, 48)));
 }
 
 // ---- the per-element arithmetic of quantize / dequantize ------------------------------

@@ -2,21 +2,23 @@
 //
 // t+1 candidate scales b_j = b_E + j (b_R - b_E)/t walk from the ACIQ estimate towards the
 // bound given by the real histogram's peak.  Each candidate is scored by the squared
-// quantization error it causes on the real tensor.  This is plain vector-ALU work
-// (about ten lane operations per element and candidate, no contraction), so the kernel is
-// organised around registers, not bandwidth:
-//   - a lane keeps 8 elements in VGPRs and runs up to 32 candidates over them; the
-//     candidates' grids are wave-uniform (scalar loads), the 32 running sums are fp64
-//     accumulators in VGPRs;
-//   - blockIdx.y selects the round (a group of cands_per_round candidates), so the whole
-//     search is one launch and the tensor is read once per round (mostly from the
-//     Infinity Cache after the first round);
-//   - per-block partial sums go to the workspace; the last block to finish (integer ticket)
-//     adds them in block order, takes the first minimum and writes the result record and
-//     the winner's quantization grid.  No floating-point atomics: bit-reproducible.
-// The per-element arithmetic is the same inline code that quantize+pack and
-// unpack+dequantize use, so a candidate's score is exactly the error of the tensor that
-// would come out of the receiver.
+// quantization error it causes on the real tensor.  This is plain vector-ALU work (eight
+// lane operations per element and candidate, no contraction), so the kernel is organised
+// around registers, not bandwidth:
+//   - the candidates are cut into rounds of (nearly) equal size; blockIdx.y selects the
+//     round, so the whole search is one launch and the tensor is read once per round
+//     (from L2 / Infinity Cache after the first);
+//   - a lane keeps 8 elements in VGPRs and runs the round's candidates over them; the
+//     candidates' grids come from LDS once and then live in wave-uniform VGPRs, the running
+//     sums are fp64 accumulators in VGPRs: the inner loop touches no memory;
+//   - the grid is sized to the number of blocks the device keeps resident (one wave of
+//     blocks, no tail);
+//   - per-block partial sums go to the workspace, candidate-major; the last block of a round
+//     (integer ticket) adds that round's partials, one wave per candidate, and the last round
+//     to finish takes the first minimum and writes the result record and the winner's grid.
+//     No floating-point atomics: bit-reproducible.
+// The per-element arithmetic is that of quantize+pack and unpack+dequantize, so a candidate's
+// score is exactly the error of the tensor that would come out of the receiver.
 #include "qp_common.hpp"
 
 namespace qp {
@@ -25,11 +27,21 @@ constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
 // One block of 256 lanes: fills the candidate table and the control record.
+//
+// It also decides whether the search may use its short per-element sequence.  The full
+// sequence clamps twice: x to [lo, hi] before the subtraction and the rounded level to
+// [0, L] after it.  With x already clamped, d = x - lo lies in [0, fl(hi - lo)], t = d*inv is
+// monotone in d (inv >= 0) and rounding is monotone, so the level lies in
+// [0, rint(fl(fl(hi - lo)*inv))]: if that upper end, evaluated here in the kernel's own fp32
+// arithmetic, is at most L for every candidate (it is whenever the range is a normal number),
+// the second clamp can never act and is dropped.  Otherwise the full sequence is used.
 __global__ __launch_bounds__(256) void k_search_setup(const qp_stats_t *__restrict__ stats_dev, double mean_h,
                                                       double b_e_h, double b_r_h, int from_ws, uint32_t bits,
                                                       uint32_t t_steps, double F, uint64_t n,
-                                                      Cand *__restrict__ cands, Ctl *__restrict__ ctl)
+                                                      Cand *__restrict__ cands, Ctl *__restrict__ ctl,
+                                                      uint32_t *__restrict__ round_tickets)
 {
+    for (uint32_t j = threadIdx.x; j <= kMaxT; j += blockDim.x) round_tickets[j] = 0u;
     double mean = mean_h, b_e = b_e_h, b_r = b_r_h;
     if (from_ws) {
         mean = stats_dev->mean;
@@ -39,15 +51,21 @@ __global__ __launch_bounds__(256) void k_search_setup(const qp_stats_t *__restri
     double step = (b_r - b_e) / (double)t_steps;
     const bool ok = (b_e > 0.0) && (b_r > 0.0) && isfinite(b_r) && isfinite(b_e) && isfinite(step);
     if (!ok) step = 0.0;   // the grid collapses onto b_E
+    const float Lf = (float)((1u << bits) - 1u);
+    int safe = 1;
     for (uint32_t j = threadIdx.x; j <= t_steps; j += blockDim.x) {
         const double b_j = b_e + (double)j * step;
         const double alpha = F * b_j;
         Cand c;
         make_grid(mean, alpha, bits, c.lo, c.hi, c.scale, c.inv_scale);
         cands[j] = c;
+        const float top = rintf((c.hi - c.lo) * c.inv_scale);
+        if (!(isfinite(c.lo) && isfinite(c.hi) && top >= 0.0f && top <= Lf)) safe = 0;
     }
+    safe = __syncthreads_and(safe);
     if (threadIdx.x == 0) {
         ctl->ticket_search = 0u;
+        ctl->short_seq = (uint32_t)safe;
         ctl->b_e = b_e;
         ctl->b_r = b_r;
         ctl->step = step;
@@ -59,31 +77,34 @@ __global__ __launch_bounds__(256) void k_search_setup(const qp_stats_t *__restri
     }
 }
 
-template <int DT>
-__global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restrict__ x, uint64_t n,
-                                                           const Cand *__restrict__ cands, uint32_t ncand,
-                                                           uint32_t cpr, float Lf, double *__restrict__ partials,
-                                                           double *__restrict__ scores, Ctl *__restrict__ ctl,
-                                                           qp_search_result_t *__restrict__ res,
-                                                           qp_qparams_t *__restrict__ best)
+// The scoring pass of one block: lanes stride over batches of kSrElems elements; for each
+// batch the round's candidates (at most 32, wave-uniform) are applied to the elements held in
+// registers.  SHORT selects the sequence without the second clamp (see k_search_setup).
+template <int DT, int CMAX, bool SHORT>
+__device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t n, const Cand *sh_cands, uint32_t nc,
+                                           float Lf, double (&acc)[CMAX])
 {
     const uint32_t tid = threadIdx.x;
-    const uint32_t c0 = blockIdx.y * cpr;
-    const uint32_t nc = min(cpr, ncand - c0);
-
-    double acc[kMaxCandsPerRound];
-#pragma unroll
-    for (int c = 0; c < (int)kMaxCandsPerRound; ++c) acc[c] = 0.0;
-
     auto score = [&](const float (&v)[kSrElems], int ne) {
 #pragma unroll
-        for (int c = 0; c < (int)kMaxCandsPerRound; ++c) {
+        for (int c = 0; c < CMAX; ++c) {
             if ((uint32_t)c < nc) {   // wave-uniform
-                const Cand p = cands[c0 + c];
+                // LDS broadcast read; the compiler hoists these out of the batch loop, so the round's
+                // grids live in (wave-uniform) VGPRs and the loop body is pure vector arithmetic
+                const Cand p = sh_cands[c];
 #pragma unroll
                 for (int e = 0; e < kSrElems; ++e) {
                     if (e < ne) {
-                        const float r = quant_level(v[e], p.lo, p.hi, p.inv_scale, Lf);
+                        float r;
+                        if constexpr (SHORT) {
+                            // med3(x, lo, hi) == min(max(x, lo), hi) for lo <= hi, NaN -> lo as well
+                            const float xc = __builtin_amdgcn_fmed3f(v[e], p.lo, p.hi);
+                            const float d = xc - p.lo;
+                            const float t = d * p.inv_scale;
+                            r = rintf(t);
+                        } else {
+                            r = quant_level(v[e], p.lo, p.hi, p.inv_scale, Lf);
+                        }
                         const float err = v[e] - dequant_level(r, p.scale, p.lo);
                         const double de = (double)err;
                         acc[c] = fma(de, de, acc[c]);   // de*de is exact in fp64
@@ -96,17 +117,16 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     const uint64_t nbatch = n / kSrElems;
     for (uint64_t b = (uint64_t)blockIdx.x * kSrThreads + tid; b < nbatch; b += (uint64_t)gridDim.x * kSrThreads) {
         float v[kSrElems];
-        float lo4[4], hi4[4];
-        Vec4<DT>::load(x, 2 * b, lo4);
-        Vec4<DT>::load(x, 2 * b + 1, hi4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            v[e] = lo4[e];
-            v[4 + e] = hi4[e];
+        for (int q = 0; q < kSrElems / 4; ++q) {
+            float f[4];
+            Vec4<DT>::load(x, (kSrElems / 4) * b + q, f);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[4 * q + e] = f[e];
         }
         score(v, kSrElems);
     }
-    // ragged tail: fewer than 8 elements, taken by one lane of block column 0
+    // ragged tail: fewer than kSrElems elements, taken by one lane of block column 0
     const uint32_t rem = (uint32_t)(n - nbatch * kSrElems);
     if (rem && blockIdx.x == 0 && tid == 0) {
         float v[kSrElems];
@@ -114,58 +134,121 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
         for (int e = 0; e < kSrElems; ++e) v[e] = ((uint32_t)e < rem) ? Vec4<DT>::load1(x, nbatch * kSrElems + e) : 0.0f;
         score(v, (int)rem);
     }
+}
 
-    // ---- block reduction: shuffles inside each wave64, one LDS row per wave ----
-    __shared__ double sh[kSrThreads / kWave][kMaxCandsPerRound];
+// CMAX: the most candidates a round can hold (sizes the register file: 2*CMAX accumulator and
+// 4*CMAX grid registers per lane).
+template <int DT, int CMAX>
+__global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restrict__ x, uint64_t n,
+                                                           const Cand *__restrict__ cands, uint32_t ncand,
+                                                           uint32_t cpr, float Lf, double *__restrict__ partials,
+                                                           double *__restrict__ scores, Ctl *__restrict__ ctl,
+                                                           uint32_t *__restrict__ round_tickets,
+                                                           qp_search_result_t *__restrict__ res,
+                                                           qp_qparams_t *__restrict__ best)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t c0 = blockIdx.y * cpr;
+    const uint32_t nc = min(cpr, ncand - c0);
+
+    double acc[CMAX];
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) acc[c] = 0.0;
+
+    // the round's candidate grids: one coalesced load into LDS, read back per candidate as a broadcast
+    __shared__ Cand sh_cands[CMAX];
+    if (tid < nc) sh_cands[tid] = cands[c0 + tid];
+    const uint32_t short_seq = ctl->short_seq;
+    __syncthreads();
+
+    if (short_seq) score_pass<DT, CMAX, true>(x, n, sh_cands, nc, Lf, acc);
+    else score_pass<DT, CMAX, false>(x, n, sh_cands, nc, Lf, acc);
+
+    // ---- block reduction: DPP inside each wave64, one LDS row per wave ----
+    __shared__ double sh[kSrThreads / kWave][CMAX];
     __shared__ uint32_t sh_flag;
     const uint32_t wave = tid / kWave, lane = tid % kWave;
+    const uint32_t gx = gridDim.x;
 #pragma unroll
-    for (int c = 0; c < (int)kMaxCandsPerRound; ++c) {
-        const double s = wave_sum(acc[c]);
-        if (lane == 0) sh[wave][c] = s;
+    for (int c = 0; c < CMAX; ++c) {
+        if ((uint32_t)c < nc) {   // wave-uniform
+            const double s = wave_sum(acc[c]);
+            if (lane == 0) sh[wave][c] = s;
+        }
     }
     __syncthreads();
     if (tid < nc) {
         double s = sh[0][tid];
         for (int w = 1; w < kSrThreads / kWave; ++w) s += sh[w][tid];
-        partials[(uint64_t)blockIdx.x * ncand + c0 + tid] = s;
+        partials[(uint64_t)(c0 + tid) * gx + blockIdx.x] = s;   // candidate-major: a candidate's partials are contiguous
     }
 
-    // ---- ticket: the last block of the whole grid finishes ----
-    // (the barrier orders all lanes' writes before lane 0's device-scope release and lane 0's
-    // acquire before all lanes' reads: one fencing lane per block, not one per wave)
+    // ---- first ticket: the last block of this round adds the round's partials ----
+    // The barrier orders every lane's global writes before lane 0's device-scope release and
+    // lane 0's acquire before every lane's reads: one fencing lane per block (a device-scope
+    // release writes the XCD's L2 back; per wave that costs more than the whole reduction).
     __syncthreads();
     if (tid == 0) {
-        const uint32_t total = gridDim.x * gridDim.y;
-        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        sh_flag = (prev == total - 1u) ? 1u : 0u;
+        const uint32_t prev = __hip_atomic_fetch_add(&round_tickets[blockIdx.y], 1u, QP_TICKET_ORDER,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        sh_flag = (prev == gx - 1u) ? 1u : 0u;
     }
     __syncthreads();
     if (!sh_flag) return;
+    QP_TICKET_ACQUIRE();
 
-    for (uint32_t j = tid; j < ncand; j += kSrThreads) {
+    // one wave per candidate: lanes stride over the blocks' partials (coalesced), fixed order
+    for (uint32_t c = wave; c < nc; c += kSrThreads / kWave) {
+        const double *__restrict__ col = partials + (uint64_t)(c0 + c) * gx;
         double s = 0.0;
-        for (uint32_t b = 0; b < gridDim.x; ++b) s += partials[(uint64_t)b * ncand + j];
-        scores[j] = s;
+        for (uint32_t b = lane; b < gx; b += kWave) s += col[b];
+        s = wave_sum(s);
+        if (lane == 0) scores[c0 + c] = s;
     }
+
+    // ---- second ticket: the last round to finish picks the winner ----
     __syncthreads();
     if (tid == 0) {
-        uint32_t bj = 0;
-        double bs = scores[0];
-        for (uint32_t j = 1; j < ncand; ++j) {
-            const double s = scores[j];
-            if (s < bs) {   // strict: ties keep the smaller j
-                bs = s;
-                bj = j;
-            }
+        round_tickets[blockIdx.y] = 0u;
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, QP_TICKET_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+        sh_flag = (prev == gridDim.y - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!sh_flag || wave != 0) return;
+    QP_TICKET_ACQUIRE();
+
+    // First minimum: a candidate replaces the incumbent only if its score is strictly lower, so
+    // ties keep the smaller index (b_E is kept unless something is strictly better) and a NaN
+    // score never wins.  Lanes scan j = lane, lane+64, ... in ascending order, then a shuffle tree.
+    double bs = INFINITY;
+    uint32_t bj = 0xffffffffu;
+    for (uint32_t j = lane; j < ncand; j += kWave) {
+        const double s = scores[j];
+        if (bj == 0xffffffffu || s < bs) {
+            bs = (s == s) ? s : INFINITY;
+            bj = j;
         }
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const double os = __shfl_xor(bs, o, kWave);
+        const uint32_t oj = __shfl_xor(bj, o, kWave);
+        if (os < bs || (os == bs && oj < bj)) {
+            bs = os;
+            bj = oj;
+        }
+    }
+    if (lane == 0) {
+        const double s0 = scores[0];
+        if (!(s0 == s0)) bj = 0u;   // a NaN incumbent is never beaten
+        const double sbest = scores[bj];
         qp_search_result_t r;
         r.b_e = ctl->b_e;
         r.b_r = ctl->b_r;
         r.b_star = ctl->b_e + (double)bj * ctl->step;
         r.alpha_star = ctl->F * r.b_star;
-        r.mse_aciq = scores[0] / (double)n;
-        r.mse_star = bs / (double)n;
+        r.mse_aciq = s0 / (double)n;
+        r.mse_star = sbest / (double)n;
         r.j_star = bj;
         r.t_steps = ncand - 1u;
         *res = r;
@@ -179,13 +262,68 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     }
 }
 
+// Upper bound on the number of block columns (sizes the partial-sum region of the workspace).
 uint32_t search_blocks(uint64_t n)
 {
     const uint64_t nbatch = n / kSrElems;
     uint32_t nb = ceil_div_u64(nbatch, kSrThreads);
     if (nb < 1) nb = 1;
-    if (nb > 512) nb = 512;
+    if (nb > kMaxSearchBlocks) nb = kMaxSearchBlocks;
     return nb;
+}
+
+// Blocks of the search kernel that the device keeps resident at once (all CUs, at the kernel's
+// own occupancy); the grid is sized to this so that there is one wave of blocks and no tail.
+template <int DT, int CMAX> static uint32_t resident_blocks()
+{
+    static uint32_t cached[16] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
+    if (cached[dev] == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_search_mse<DT, CMAX>, kSrThreads, 0) != hipSuccess ||
+            per_cu < 1)
+            per_cu = 2;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        cached[dev] = (uint32_t)per_cu * (uint32_t)cus;
+    }
+    return cached[dev];
+}
+
+struct SearchArgs {
+    const void *x;
+    uint64_t n;
+    const Cand *cands;
+    uint32_t ncand, cpr;
+    float Lf;
+    double *partials, *scores;
+    Ctl *ctl;
+    uint32_t *round_tickets;
+    qp_search_result_t *res;
+    qp_qparams_t *best;
+};
+
+// Picks the round structure and the grid for one kernel variant and launches it.
+template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a, uint32_t cpr_limit, hipStream_t s)
+{
+    // Rounds of (nearly) equal size: 101 candidates at 16 per round -> 15,15,15,14,14,14,14.  A tensor
+    // too small to fill the device with that many rounds is cut into more, shorter rounds instead
+    // (the caller's cands_per_round is an upper bound and never changes results).
+    const uint32_t resident = resident_blocks<DT, CMAX>();
+    const uint32_t cols = search_blocks(a.n);
+    uint32_t rounds = (a.ncand + cpr_limit - 1u) / cpr_limit;
+    if (cols * rounds < resident) {
+        rounds = resident / cols;
+        if (rounds > a.ncand) rounds = a.ncand;
+    }
+    const uint32_t cpr_eff = (a.ncand + rounds - 1u) / rounds;
+    rounds = (a.ncand + cpr_eff - 1u) / cpr_eff;   // no empty round
+    uint32_t gx = resident / rounds;
+    if (gx > cols) gx = cols;
+    if (gx < 1) gx = 1;
+    hipLaunchKernelGGL((k_search_mse<DT, CMAX>), dim3(gx, rounds), dim3(kSrThreads), 0, s, a.x, a.n, a.cands, a.ncand,
+                       cpr_eff, a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best);
+    return hipGetLastError();
 }
 
 hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
@@ -194,28 +332,22 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
-    double *scores = reinterpret_cast<double *>(w + kOffScores);
-    double *partials = reinterpret_cast<double *>(w + kOffSearchPart);
     qp_stats_t *stats_dev = reinterpret_cast<qp_stats_t *>(w + kOffStats);
-    qp_search_result_t *res = reinterpret_cast<qp_search_result_t *>(w + kOffResult);
-    qp_qparams_t *best = reinterpret_cast<qp_qparams_t *>(w + kOffQParams);
+    uint32_t *round_tickets = reinterpret_cast<uint32_t *>(w + kOffRoundTickets);
 
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(256), 0, s, stats_dev, st ? st->mean : 0.0, st ? st->mad : 0.0,
-                       st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl);
+                       st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    const uint32_t ncand = t_steps + 1u;
-    const uint32_t rounds = (ncand + cpr - 1u) / cpr;
-    const dim3 grid(search_blocks(n), rounds);
-    const float Lf = (float)((1u << bits) - 1u);
-    if (dtype == QP_F32)
-        hipLaunchKernelGGL(k_search_mse<QP_F32>, grid, dim3(kSrThreads), 0, s, x, n, cands, ncand, cpr, Lf, partials,
-                           scores, ctl, res, best);
-    else
-        hipLaunchKernelGGL(k_search_mse<QP_BF16>, grid, dim3(kSrThreads), 0, s, x, n, cands, ncand, cpr, Lf, partials,
-                           scores, ctl, res, best);
-    return hipGetLastError();
+    SearchArgs a{x, n, cands, t_steps + 1u, cpr, (float)((1u << bits) - 1u),
+                 reinterpret_cast<double *>(w + kOffSearchPart), reinterpret_cast<double *>(w + kOffScores), ctl,
+                 round_tickets, reinterpret_cast<qp_search_result_t *>(w + kOffResult),
+                 reinterpret_cast<qp_qparams_t *>(w + kOffQParams)};
+    // the 16-candidate variant keeps three waves per SIMD resident, the 32-candidate one two
+    if (cpr <= 16u)
+        return dtype == QP_F32 ? launch_variant<QP_F32, 16>(a, cpr, s) : launch_variant<QP_BF16, 16>(a, cpr, s);
+    return dtype == QP_F32 ? launch_variant<QP_F32, 32>(a, cpr, s) : launch_variant<QP_BF16, 32>(a, cpr, s);
 }
 
 }  // namespace qp

@@ -4,7 +4,7 @@
 // Two streaming passes, both HBM-bound (4 B per fp32 element each):
 //   pass 1  sum, sum|x|, min, max, NaN/Inf count        -> one partial per block
 //   pass 2  sum|x - mu|, sum (x - mu)^2, histogram      -> partial per block + LDS histogram
-// Accumulation is fp64 per lane, reduced with wave64 shuffles, one LDS slot per wave,
+// Accumulation is fp64 per lane, reduced inside each wave64 with DPP lane permutations, one LDS slot per wave,
 // then across blocks in index order: no floating-point atomics, so results are
 // bit-reproducible from run to run.  Pass 2 needs mu, min and max; every block of pass 2
 // re-reduces the (at most 1024) pass-1 partials itself, which removes one launch and one
@@ -216,11 +216,12 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
     // (a device-scope release writes this XCD's L2 back, which is far too dear to do per wave).
     __syncthreads();
     if (tid == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_stats2, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_stats2, 1u, QP_TICKET_ORDER, __HIP_MEMORY_SCOPE_AGENT);
         sh_flag = (prev == gridDim.x - 1u) ? 1u : 0u;
     }
     __syncthreads();
     if (!sh_flag) return;
+    QP_TICKET_ACQUIRE();
 
     // pass-2 partials in block order, split over the lanes of the block in a fixed pattern
     Part2 q{0.0, 0.0};

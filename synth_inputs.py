@@ -175,4 +175,6 @@ def edge_cases(seed: int = 7):
     out.append(("tiny_values", (rng.laplace(0.0, 1.0, size=3000) * 1e-30).astype(np.float32)))
     out.append(("large_values", (rng.laplace(0.0, 1.0, size=3000) * 1e30).astype(np.float32)))
     out.append(("ramp", np.arange(6000, dtype=np.float32)))
+    # so small that the clipping range is a subnormal float and its reciprocal overflows
+    out.append(("subnormal_values", (rng.laplace(0.0, 1.0, size=3000) * 1e-41).astype(np.float32)))
     return out

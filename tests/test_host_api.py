@@ -61,7 +61,7 @@ def test_packed_bytes(qp):
 
 def test_workspace_bytes(qp):
     cfg = qp.qp_default_search_cfg()
-    assert (cfg.t_steps, cfg.cands_per_round, cfg.nbins, cfg.dist) == (100, 32, 2048, qp.QP_LAPLACE)
+    assert (cfg.t_steps, cfg.cands_per_round, cfg.nbins, cfg.dist) == (100, 13, 2048, qp.QP_LAPLACE)
     a = qp.qp_workspace_bytes(9_682_944)
     assert a == qp.qp_workspace_bytes(9_682_944, cfg) and a > qp.qp_ws_offset(qp.QP_WS_SCORES)
     cfg.t_steps = 1000
