@@ -28,13 +28,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0                  # MI355X HBM3E, published
-VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz: one vector op per lane per clock
+# Vector-ALU peak for the search kernel's operation mix.  Published vector peaks: fp32 157.3 TFLOP/s
+# and fp64 78.6 TFLOP/s, i.e. (an FMA counting two flops) 78.64e12 fp32 and 39.32e12 fp64 lane
+# operations per second (256 CUs x 2.4 GHz x 128 resp. 64 lanes).  Per element and candidate the
+# search does 6 fp32 operations (clamp, subtract, multiply, round, fma, subtract) and 2 fp64-class
+# ones (convert, fma): at peak that takes 6/78.64e12 + 2/39.32e12 s, so 8 operations run at
+# 8 / (6/78.64 + 2/39.32) = 62.9e12 lane operations per second at best.
 SEARCH_LANEOPS_PER_ELEM_CAND = 8       # algorithmic vector operations per element and candidate
+VALU_PEAK_TLANEOPS = 8.0 / (6.0 / 78.64 + 2.0 / 39.32)
 NBUF = 16
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
-# None where no counter run has been committed for that kernel yet.
-TRAFFIC_BYTES = {"search": None, "pack": None, "unpack": None, "stats": None}
+# HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload, scaled by
+# what the same counters read for plain device copies of the tensor in the same run (summary and
+# commands: profiles/hbm_traffic_C2_fp32.txt).  pack / unpack: mean over the six bitwidths.
+TRAFFIC_BYTES = {"search": 40.72e6, "pack": 46.61e6, "unpack": 46.74e6, "stats": 78.10e6}
 
 
 def main() -> int:
@@ -43,6 +50,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-large", action="store_true", help="skip the 151M-element bf16 tensor leg")
     ap.add_argument("--kernel-reps", type=int, default=64, help="back-to-back launches per kernel timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -99,6 +107,10 @@ def main() -> int:
         for b in bits_set:
             one_pass(b, timers)
 
+    # four plain device copies of the tensor: under a rocprofv3 counter run these calibrate what
+    # FETCH_SIZE / WRITE_SIZE read for a kernel that moves a known number of bytes
+    for i in range(4):
+        ys[i].copy_(xs[i])
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -164,6 +176,14 @@ def main() -> int:
     r_unpack = hbm("k_unpack_dequant<k>, k in {2,3,4,6,8,16}", pack_bytes / len(bits_set), unpack_us / len(bits_set), "unpack")
     r_stats = hbm("k_stats_pass1 + k_stats_pass2", 2 * in_bytes, ts, "stats")
 
+    # the large bf16 tensor (256x577x1024, 302 MB in: larger than the Infinity Cache by itself):
+    # the HBM-honest reading of the same two kernels, kernel-only
+    large = None
+    if not args.no_large:
+        del xs, ys, packs
+        torch.cuda.empty_cache()
+        large = large_tensor_leg(qp, si, torch, timed_reps, args.kernel_reps)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(x_host, bits_set)
@@ -180,10 +200,38 @@ def main() -> int:
         "dsaciq_us_per_tensor": search_us,
         "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
         "per_bitwidth": per_bits,
+        "large_tensor_bf16": large,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
     return 0
+
+
+def large_tensor_leg(qp, si, torch, timed_reps, reps):
+    """quantize+pack and unpack+dequantize on the 256x577x1024 bf16 tensor (Student-t, df 3, x0.5)."""
+    h = si.make_config("C5")
+    n = h.size
+    nb = 3
+    xs = [torch.from_numpy(h.view("int16").copy()).cuda().view(torch.bfloat16) for _ in range(nb)]
+    ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(nb)]
+    ws = qp.alloc_workspace(n)
+    st = qp.qp_stats(xs[0], ws)
+    out = {"elements": n, "input": "bf16", "buffers_rotated": nb, "stats_us": None}
+    out["stats_us"] = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
+    out["stats_GBs"] = 2 * n * 2 / out["stats_us"] / 1e3
+    for b in si.CONFIG_BITS["C5"]:
+        packs = [qp.alloc_packed(n, b) for _ in range(nb)]
+        res, q = qp.qp_dsaciq_search(xs[0], st, b, ws)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % nb]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % nb], q, ys[r % nb]))
+        ts = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], b, ws)) if b == 4 else None
+        bp, bu = n * 2 + n * b / 8, n * 4 + n * b / 8
+        out[str(b)] = {"pack_us": tp, "pack_GBs": bp / tp / 1e3, "pack_frac_hbm": bp / tp / 1e3 / HBM_PEAK_GBS,
+                       "unpack_us": tu, "unpack_GBs": bu / tu / 1e3, "unpack_frac_hbm": bu / tu / 1e3 / HBM_PEAK_GBS}
+        if ts:
+            out["dsaciq_us_per_tensor"] = ts
+        del packs
+    return out
 
 
 def cpu_baseline(x_host, bits_set):

@@ -282,11 +282,17 @@ hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, vo
     uint32_t *hist = reinterpret_cast<uint32_t *>(w + kOffHist);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
     qp_stats_t *out = reinterpret_cast<qp_stats_t *>(w + kOffStats);
+    // Whole tiles per block: with T tiles and at most B blocks, every block takes ceil(T/B) tiles
+    // and the grid shrinks to the number of blocks that this needs, so that no block runs one
+    // tile more than the rest.
     const uint64_t nvec = n / 4;
-    uint32_t nb1 = ceil_div_u64(nvec, (uint64_t)kS1Threads * kS1Unroll);
-    nb1 = nb1 < 1 ? 1 : (nb1 > kMaxStat1Blocks ? kMaxStat1Blocks : nb1);
-    uint32_t nb2 = ceil_div_u64(nvec, (uint64_t)kS2Threads * kS2Unroll);
-    nb2 = nb2 < 1 ? 1 : (nb2 > kMaxStat2Blocks ? kMaxStat2Blocks : nb2);
+    auto even_grid = [](uint64_t tiles, uint32_t max_blocks) -> uint32_t {
+        if (tiles < 1) return 1u;
+        const uint64_t per = (tiles + max_blocks - 1) / max_blocks;
+        return (uint32_t)((tiles + per - 1) / per);
+    };
+    const uint32_t nb1 = even_grid((nvec + kS1Threads * kS1Unroll - 1) / (kS1Threads * kS1Unroll), kMaxStat1Blocks);
+    const uint32_t nb2 = even_grid((nvec + kS2Threads * kS2Unroll - 1) / (kS2Threads * kS2Unroll), kMaxStat2Blocks);
     if (dtype == QP_F32) {
         hipLaunchKernelGGL(k_stats_pass1<QP_F32>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
         hipLaunchKernelGGL(k_stats_pass2<QP_F32>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins,
