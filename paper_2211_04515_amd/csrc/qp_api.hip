@@ -118,7 +118,7 @@ qp_status qp_stats_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t
         return QP_EINVAL;
     if (!ws_dev || !aligned16(ws_dev)) return QP_EINVAL;
     if (ws_bytes < kOffSearchPart) return QP_ENOSPC;   // the statistics use only the fixed-size head
-    return hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), true));
 }
 
 qp_status qp_stats(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t nbins, void *ws_dev, size_t ws_bytes,
@@ -163,7 +163,8 @@ qp_status qp_make_qparams(double center, double alpha, uint32_t bits, uint64_t n
 }
 
 static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats, uint32_t bits,
-                               const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream)
+                               const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream,
+                               uint32_t finalize_nbins = 0)
 {
     if (!x_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || !bits_ok(bits) || !aligned16(x_dev)) return QP_EINVAL;
     if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
@@ -171,8 +172,8 @@ static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, co
     if (w != QP_OK) return w;
     const uint32_t t = cfg ? cfg->t_steps : 100u;
     const uint32_t cpr = cfg ? cfg->cands_per_round : 13u;
-    return hip_status(launch_search(x_dev, n, dtype, bits, t, cpr, laplace_constant(bits), stats, ws_dev,
-                                    static_cast<hipStream_t>(stream)));
+    return hip_status(launch_search(x_dev, n, dtype, bits, t, cpr, laplace_constant(bits), stats, finalize_nbins,
+                                    ws_dev, static_cast<hipStream_t>(stream)));
 }
 
 qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
@@ -254,11 +255,15 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     if (!packed_dev || !bits_ok(bits) || !aligned16(packed_dev)) return QP_EINVAL;
     if (packed_bytes < qp_packed_bytes(n, bits)) return QP_ENOSPC;
     const uint32_t nbins = (cfg && cfg->nbins) ? cfg->nbins : 2048u;
+    if (!x_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || nbins < 16 || nbins > kMaxBins || !aligned16(x_dev))
+        return QP_EINVAL;
+    if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
     qp_status st = check_ws(n, cfg, ws_dev, ws_bytes);
     if (st != QP_OK) return st;
-    st = qp_stats_async(x_dev, n, dtype, nbins, ws_dev, ws_bytes, stream);
+    // the two statistics passes leave partials; the search's set-up kernel finalizes them
+    st = hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), false));
     if (st != QP_OK) return st;
-    st = qp_dsaciq_search_async(x_dev, n, dtype, bits, cfg, ws_dev, ws_bytes, stream);
+    st = search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream, nbins);
     if (st != QP_OK) return st;
     const qp_qparams_t *qdev = reinterpret_cast<const qp_qparams_t *>(static_cast<char *>(ws_dev) + kOffQParams);
     st = qp_quant_pack_dev(x_dev, n, dtype, bits, qdev, packed_dev, packed_bytes, stream);

@@ -42,8 +42,8 @@ static_assert(sizeof(Cand) == 16, "Cand layout");
 
 // Device-resident control block.
 struct Ctl {
-    uint32_t ticket_stats2;   // blocks of the second statistics pass that have finished
-    uint32_t ticket_search;   // blocks of the search kernel that have finished
+    uint32_t reserved0;
+    uint32_t ticket_search;   // rounds of the search kernel that have finished
     uint32_t short_seq;       // 1: the search may drop the clamp of the rounded level
     uint32_t pad1;
     double b_e, b_r, step, F; // search grid: b_j = b_e + j*step, alpha_j = F*b_j
@@ -229,6 +229,103 @@ __device__ __forceinline__ float dequant_level(float c, float scale, float lo)
     return __builtin_fmaf(c, scale, lo);
 }
 
+// ---- statistics: partials -> record ------------------------------------------------------
+// Run by one whole block of kFinThreads lanes after both streaming passes have completed (a
+// kernel boundary, so no fences are needed).  Everything is added in a fixed order.
+constexpr int kFinThreads = 512;   // same block size as pass 2, so that both reduce the pass-1 partials identically
+
+// Sum of the pass-1 partials over one block of T lanes, in an order that depends only on T:
+// pass 2 (for mu, min, max) and the finalizer (for the record) get bit-identical values.
+template <int T>
+__device__ __forceinline__ Part1 reduce_part1_block(const Part1 *__restrict__ part1, uint32_t nb1, Part1 *sh /*[T / 64]*/)
+{
+    const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    Part1 t{0.0, 0.0, INFINITY, -INFINITY, 0u, 0u};
+    for (uint32_t i = tid; i < nb1; i += T) {
+        const Part1 p = part1[i];
+        t.sum += p.sum;
+        t.sum_abs += p.sum_abs;
+        t.mn = fminf(t.mn, p.mn);
+        t.mx = fmaxf(t.mx, p.mx);
+        t.bad += p.bad;
+    }
+    t.sum = wave_sum(t.sum);
+    t.sum_abs = wave_sum(t.sum_abs);
+    t.mn = wave_min(t.mn);
+    t.mx = wave_max(t.mx);
+    t.bad = wave_sum_u32(t.bad);
+    if (lane == 0) sh[wave] = t;
+    __syncthreads();
+    Part1 tot = sh[0];
+#pragma unroll
+    for (int w = 1; w < T / kWave; ++w) {
+        tot.sum += sh[w].sum;
+        tot.sum_abs += sh[w].sum_abs;
+        tot.mn = fminf(tot.mn, sh[w].mn);
+        tot.mx = fmaxf(tot.mx, sh[w].mx);
+        tot.bad += sh[w].bad;
+    }
+    return tot;
+}
+
+__device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uint32_t nb1,
+                                            const Part2 *__restrict__ part2, uint32_t nb2,
+                                            const uint32_t *__restrict__ hist, uint32_t nbins, uint64_t n,
+                                            qp_stats_t *__restrict__ out)
+{
+    __shared__ Part1 f1[kFinThreads / kWave];
+    __shared__ Part2 f2[kFinThreads / kWave];
+    __shared__ uint32_t fpk[kFinThreads / kWave];
+    const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const Part1 a = reduce_part1_block<kFinThreads>(part1, nb1, f1);
+    Part2 q{0.0, 0.0};
+    for (uint32_t i = tid; i < nb2; i += kFinThreads) {
+        const Part2 p = part2[i];
+        q.dev += p.dev;
+        q.sq += p.sq;
+    }
+    uint32_t peak = 0u;
+    for (uint32_t b = tid; b < nbins; b += kFinThreads) peak = max(peak, hist[b]);
+    q.dev = wave_sum(q.dev);
+    q.sq = wave_sum(q.sq);
+    peak = wave_max_u32(peak);
+    if (lane == 0) {
+        f2[wave] = q;
+        fpk[wave] = peak;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        Part2 b = f2[0];
+        uint32_t pk = fpk[0];
+        for (int w = 1; w < kFinThreads / kWave; ++w) {
+            b.dev += f2[w].dev;
+            b.sq += f2[w].sq;
+            pk = max(pk, fpk[w]);
+        }
+        qp_stats_t st;
+        st.n = n;
+        st.n_nonfinite = a.bad;
+        st.mean = a.sum / (double)n;
+        st.mad = b.dev / (double)n;
+        st.abs_mean = a.sum_abs / (double)n;
+        st.var = b.sq / (double)n;
+        st.min = (double)a.mn;
+        st.max = (double)a.mx;
+        st.nbins = nbins;
+        st.peak_count = pk;
+        if (a.mx == a.mn) {   // one distinct value: the density peak is unbounded, the bound is 0
+            st.peak_density = 0.0;
+            st.b_r = 0.0;
+        } else {
+            const double binw = ((double)a.mx - (double)a.mn) / (double)nbins;
+            st.peak_density = (double)pk / ((double)n * binw);
+            st.b_r = 1.0 / (2.0 * st.peak_density);
+        }
+        *out = st;
+    }
+    __syncthreads();   // the record is visible to the whole block from here on
+}
+
 // The grid a clipping threshold induces; same statement as qp_make_qparams on the host.
 __device__ __host__ inline void make_grid(double center, double alpha, uint32_t bits, float &lo, float &hi,
                                           float &scale, float &inv_scale)
@@ -251,9 +348,17 @@ __device__ __host__ inline void make_grid(double center, double alpha, uint32_t 
 inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 
 // Kernel launchers (one per translation unit); all return hipError_t from hipGetLastError().
-hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s);
+// The two streaming passes of the statistics; `finalize` adds the one-block kernel that turns the
+// partials into the qp_stats_t record (left out when the search set-up kernel will do it).
+hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s, bool finalize);
+void stats_grid(uint64_t n, uint32_t &nb1, uint32_t &nb2);
+// Set-up + search.  stats_host_or_null: statistics from the host, else they are taken from the
+// workspace; finalize_nbins != 0: the set-up kernel first finalizes the statistics that
+// launch_stats(..., finalize = false) left as partials (histogram of finalize_nbins bins).
 hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
-                         double F, const qp_stats_t *stats_host_or_null, void *ws, hipStream_t s);
+                         double F, const qp_stats_t *stats_host_or_null, uint32_t finalize_nbins, void *ws,
+                         hipStream_t s);
+hipError_t launch_stats_finalize(uint64_t n, uint32_t nbins, void *ws, hipStream_t s);
 uint32_t search_blocks(uint64_t n);
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *host_qp,
                              const qp_qparams_t *dev_qp, void *packed, hipStream_t s);

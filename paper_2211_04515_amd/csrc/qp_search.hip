@@ -26,7 +26,7 @@ namespace qp {
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
-// One block of 256 lanes: fills the candidate table and the control record.
+// One block: fills the candidate table and the control record.
 //
 // It also decides whether the search may use its short per-element sequence.  The full
 // sequence clamps twice: x to [lo, hi] before the subtraction and the rounded level to
@@ -35,13 +35,24 @@ constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vect
 // [0, rint(fl(fl(hi - lo)*inv))]: if that upper end, evaluated here in the kernel's own fp32
 // arithmetic, is at most L for every candidate (it is whenever the range is a normal number),
 // the second clamp can never act and is dropped.  Otherwise the full sequence is used.
-__global__ __launch_bounds__(256) void k_search_setup(const qp_stats_t *__restrict__ stats_dev, double mean_h,
-                                                      double b_e_h, double b_r_h, int from_ws, uint32_t bits,
-                                                      uint32_t t_steps, double F, uint64_t n,
-                                                      Cand *__restrict__ cands, Ctl *__restrict__ ctl,
-                                                      uint32_t *__restrict__ round_tickets)
+//
+// When the statistics passes have only left their partials (the fused sender path), this block
+// first turns them into the qp_stats_t record, which saves a launch.
+struct FinalizeArgs {
+    const Part1 *part1;
+    const Part2 *part2;
+    const uint32_t *hist;
+    uint32_t nb1, nb2, nbins;   // nbins == 0: nothing to finalize
+};
+
+__global__ __launch_bounds__(kFinThreads) void k_search_setup(qp_stats_t *__restrict__ stats_dev, double mean_h,
+                                                              double b_e_h, double b_r_h, int from_ws, uint32_t bits,
+                                                              uint32_t t_steps, double F, uint64_t n,
+                                                              Cand *__restrict__ cands, Ctl *__restrict__ ctl,
+                                                              uint32_t *__restrict__ round_tickets, FinalizeArgs fin)
 {
     for (uint32_t j = threadIdx.x; j <= kMaxT; j += blockDim.x) round_tickets[j] = 0u;
+    if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
     double mean = mean_h, b_e = b_e_h, b_r = b_r_h;
     if (from_ws) {
         mean = stats_dev->mean;
@@ -327,7 +338,7 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
 }
 
 hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
-                         double F, const qp_stats_t *st, void *ws, hipStream_t s)
+                         double F, const qp_stats_t *st, uint32_t finalize_nbins, void *ws, hipStream_t s)
 {
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
@@ -335,8 +346,12 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
     qp_stats_t *stats_dev = reinterpret_cast<qp_stats_t *>(w + kOffStats);
     uint32_t *round_tickets = reinterpret_cast<uint32_t *>(w + kOffRoundTickets);
 
-    hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(256), 0, s, stats_dev, st ? st->mean : 0.0, st ? st->mad : 0.0,
-                       st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets);
+    FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
+                     reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
+    if (finalize_nbins) stats_grid(n, fin.nb1, fin.nb2);
+    hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, stats_dev, st ? st->mean : 0.0,
+                       st ? st->mad : 0.0, st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets,
+                       fin);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -344,7 +359,8 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
                  reinterpret_cast<double *>(w + kOffSearchPart), reinterpret_cast<double *>(w + kOffScores), ctl,
                  round_tickets, reinterpret_cast<qp_search_result_t *>(w + kOffResult),
                  reinterpret_cast<qp_qparams_t *>(w + kOffQParams)};
-    // the 16-candidate variant keeps three waves per SIMD resident, the 32-candidate one two
+    // the 16-candidate variant keeps three waves per SIMD resident, the 32-candidate one two (forcing more
+    // waves only makes the compiler spill the accumulators)
     if (cpr <= 16u)
         return dtype == QP_F32 ? launch_variant<QP_F32, 16>(a, cpr, s) : launch_variant<QP_BF16, 16>(a, cpr, s);
     return dtype == QP_F32 ? launch_variant<QP_F32, 32>(a, cpr, s) : launch_variant<QP_BF16, 32>(a, cpr, s);

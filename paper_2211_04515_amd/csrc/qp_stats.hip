@@ -4,12 +4,14 @@
 // Two streaming passes, both HBM-bound (4 B per fp32 element each):
 //   pass 1  sum, sum|x|, min, max, NaN/Inf count        -> one partial per block
 //   pass 2  sum|x - mu|, sum (x - mu)^2, histogram      -> partial per block + LDS histogram
-// Accumulation is fp64 per lane, reduced inside each wave64 with DPP lane permutations, one LDS slot per wave,
-// then across blocks in index order: no floating-point atomics, so results are
-// bit-reproducible from run to run.  Pass 2 needs mu, min and max; every block of pass 2
-// re-reduces the (at most 1024) pass-1 partials itself, which removes one launch and one
-// grid-wide dependency.  The last block of pass 2 to finish (an integer ticket) reduces
-// the pass-2 partials, finds the histogram peak and writes the qp_stats_t record.
+// Accumulation is fp64 per lane, reduced inside each wave64 with DPP lane permutations, one
+// LDS slot per wave, then across blocks in a fixed order: no floating-point atomics, so
+// results are bit-reproducible from run to run.  Pass 2 needs mu, min and max; every block of
+// pass 2 re-reduces the (at most 1024) pass-1 partials itself, with its first loads of the
+// tensor already in flight, which saves a launch and a grid-wide dependency.  A one-block
+// kernel after pass 2 (or the search's set-up kernel, when the search follows) turns the
+// partials and the histogram into the qp_stats_t record: kernel boundaries order the memory,
+// so neither pass needs a fence.
 #include "qp_common.hpp"
 
 namespace qp {
@@ -44,10 +46,7 @@ __global__ __launch_bounds__(kS1Threads) void k_stats_pass1(const void *__restri
     // Clear what pass 2 and the search accumulate into (they run after this kernel on the stream).
     if (blockIdx.x == 0) {
         for (uint32_t b = tid; b < nbins; b += kS1Threads) hist[b] = 0u;
-        if (tid == 0) {
-            ctl->ticket_stats2 = 0u;
-            ctl->ticket_search = 0u;
-        }
+        if (tid == 0) ctl->ticket_search = 0u;
     }
 
     Acc1 a0{0.0, 0.0, INFINITY, -INFINITY, 0u};
@@ -109,45 +108,32 @@ template <int DT>
 __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restrict__ x, uint64_t n,
                                                             const Part1 *__restrict__ part1, uint32_t nb1,
                                                             Part2 *__restrict__ part2, uint32_t *__restrict__ hist,
-                                                            uint32_t nbins, Ctl *__restrict__ ctl,
-                                                            qp_stats_t *__restrict__ out)
+                                                            uint32_t nbins)
 {
     __shared__ uint32_t sh_hist[kMaxBins];
     __shared__ Part1 sh1[kS2Threads / kWave];
     __shared__ Part2 sh2[kS2Threads / kWave];
-    __shared__ uint32_t sh_flag;
-    __shared__ uint32_t sh_peak[kS2Threads / kWave];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid / kWave, lane = tid % kWave;
 
     for (uint32_t b = tid; b < nbins; b += kS2Threads) sh_hist[b] = 0u;
 
-    // ---- every block reduces the pass-1 partials in the same fixed order ----
-    Part1 t{0.0, 0.0, INFINITY, -INFINITY, 0u, 0u};
-    for (uint32_t i = tid; i < nb1; i += kS2Threads) {
-        const Part1 p = part1[i];
-        t.sum += p.sum;
-        t.sum_abs += p.sum_abs;
-        t.mn = fminf(t.mn, p.mn);
-        t.mx = fmaxf(t.mx, p.mx);
-        t.bad += p.bad;
-    }
-    t.sum = wave_sum(t.sum);
-    t.sum_abs = wave_sum(t.sum_abs);
-    t.mn = wave_min(t.mn);
-    t.mx = wave_max(t.mx);
-    t.bad = wave_sum_u32(t.bad);
-    if (lane == 0) sh1[wave] = t;
-    __syncthreads();
-    Part1 tot = sh1[0];
+    // the block's first tile is requested before anything else, so that the tensor is already
+    // streaming while the pass-1 partials are being reduced
+    const uint64_t nvec = n / 4;
+    const uint64_t tile = (uint64_t)kS2Threads * kS2Unroll;
+    uint64_t base = (uint64_t)blockIdx.x * tile;
+    const uint64_t stride = (uint64_t)gridDim.x * tile;
+    float pre[kS2Unroll][4];
+    const bool have_pre = base + tile <= nvec;
+    if (have_pre) {
 #pragma unroll
-    for (int w = 1; w < kS2Threads / kWave; ++w) {
-        tot.sum += sh1[w].sum;
-        tot.sum_abs += sh1[w].sum_abs;
-        tot.mn = fminf(tot.mn, sh1[w].mn);
-        tot.mx = fmaxf(tot.mx, sh1[w].mx);
-        tot.bad += sh1[w].bad;
+        for (int u = 0; u < kS2Unroll; ++u) Vec4<DT>::load(x, base + (uint64_t)u * kS2Threads + tid, pre[u]);
     }
+
+    // ---- every block reduces the pass-1 partials in the same fixed order ----
+    static_assert(kS2Threads == kFinThreads, "pass 2 and the finalizer must reduce the partials identically");
+    const Part1 tot = reduce_part1_block<kS2Threads>(part1, nb1, sh1);
     const double mean = tot.sum / (double)n;
     const float mn = tot.mn, mx = tot.mx;
     // bin index arithmetic in fp32: one subtraction and one division here (the fp64 quotient of
@@ -166,10 +152,16 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
         const uint32_t idx = (uint32_t)fminf(fmaxf(tt, 0.0f), top);   // NaN (0*inf) -> 0
         atomicAdd(&sh_hist[idx], 1u);
     };
-    const uint64_t nvec = n / 4;
-    const uint64_t tile = (uint64_t)kS2Threads * kS2Unroll;
-    uint64_t base = (uint64_t)blockIdx.x * tile;
-    const uint64_t stride = (uint64_t)gridDim.x * tile;
+    if (have_pre) {
+#pragma unroll
+        for (int u = 0; u < kS2Unroll; ++u) {
+            add(pre[u][0], dev0, sq0);
+            add(pre[u][1], dev1, sq1);
+            add(pre[u][2], dev0, sq0);
+            add(pre[u][3], dev1, sq1);
+        }
+        base += stride;
+    }
     for (; base + tile <= nvec; base += stride) {
         float f[kS2Unroll][4];
 #pragma unroll
@@ -210,99 +202,61 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
         }
         part2[blockIdx.x] = p;
     }
-    // ---- ticket: the last block to arrive finishes the job ----
-    // The barrier orders every lane's global writes before lane 0's device-scope release, and
-    // lane 0's acquire before every lane's reads below; one lane fences instead of all of them
-    // (a device-scope release writes this XCD's L2 back, which is far too dear to do per wave).
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_stats2, 1u, QP_TICKET_ORDER, __HIP_MEMORY_SCOPE_AGENT);
-        sh_flag = (prev == gridDim.x - 1u) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!sh_flag) return;
-    QP_TICKET_ACQUIRE();
-
-    // pass-2 partials in block order, split over the lanes of the block in a fixed pattern
-    Part2 q{0.0, 0.0};
-    for (uint32_t i = tid; i < gridDim.x; i += kS2Threads) {
-        const Part2 p = part2[i];
-        q.dev += p.dev;
-        q.sq += p.sq;
-    }
-    q.dev = wave_sum(q.dev);
-    q.sq = wave_sum(q.sq);
-    uint32_t peak = 0u;
-    for (uint32_t b = tid; b < nbins; b += kS2Threads)
-        peak = max(peak, __hip_atomic_load(&hist[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    peak = wave_max_u32(peak);
-    __syncthreads();
-    if (lane == 0) {
-        sh2[wave] = q;
-        sh_peak[wave] = peak;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        Part2 p = sh2[0];
-        uint32_t pk = sh_peak[0];
-        for (int w = 1; w < kS2Threads / kWave; ++w) {
-            p.dev += sh2[w].dev;
-            p.sq += sh2[w].sq;
-            pk = max(pk, sh_peak[w]);
-        }
-        qp_stats_t st;
-        st.n = n;
-        st.n_nonfinite = tot.bad;
-        st.mean = mean;
-        st.mad = p.dev / (double)n;
-        st.abs_mean = tot.sum_abs / (double)n;
-        st.var = p.sq / (double)n;
-        st.min = (double)mn;
-        st.max = (double)mx;
-        st.nbins = nbins;
-        st.peak_count = pk;
-        if (mx == mn) {
-            st.peak_density = 0.0;
-            st.b_r = 0.0;
-        } else {
-            const double binw = ((double)mx - (double)mn) / (double)nbins;
-            st.peak_density = (double)pk / ((double)n * binw);
-            st.b_r = 1.0 / (2.0 * st.peak_density);
-        }
-        *out = st;
-        ctl->ticket_stats2 = 0u;
-    }
 }
 
-hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s)
+__global__ __launch_bounds__(kFinThreads) void k_stats_finalize(const Part1 *__restrict__ part1, uint32_t nb1,
+                                                                const Part2 *__restrict__ part2, uint32_t nb2,
+                                                                const uint32_t *__restrict__ hist, uint32_t nbins,
+                                                                uint64_t n, qp_stats_t *__restrict__ out)
 {
-    char *w = static_cast<char *>(ws);
-    Part1 *p1 = reinterpret_cast<Part1 *>(w + kOffPart1);
-    Part2 *p2 = reinterpret_cast<Part2 *>(w + kOffPart2);
-    uint32_t *hist = reinterpret_cast<uint32_t *>(w + kOffHist);
-    Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
-    qp_stats_t *out = reinterpret_cast<qp_stats_t *>(w + kOffStats);
-    // Whole tiles per block: with T tiles and at most B blocks, every block takes ceil(T/B) tiles
-    // and the grid shrinks to the number of blocks that this needs, so that no block runs one
-    // tile more than the rest.
+    finalize_stats_block(part1, nb1, part2, nb2, hist, nbins, n, out);
+}
+
+// Whole tiles per block: with T tiles and at most B blocks, every block takes ceil(T/B) tiles and
+// the grid shrinks to the number of blocks that this needs.
+void stats_grid(uint64_t n, uint32_t &nb1, uint32_t &nb2)
+{
     const uint64_t nvec = n / 4;
     auto even_grid = [](uint64_t tiles, uint32_t max_blocks) -> uint32_t {
         if (tiles < 1) return 1u;
         const uint64_t per = (tiles + max_blocks - 1) / max_blocks;
         return (uint32_t)((tiles + per - 1) / per);
     };
-    const uint32_t nb1 = even_grid((nvec + kS1Threads * kS1Unroll - 1) / (kS1Threads * kS1Unroll), kMaxStat1Blocks);
-    const uint32_t nb2 = even_grid((nvec + kS2Threads * kS2Unroll - 1) / (kS2Threads * kS2Unroll), kMaxStat2Blocks);
+    nb1 = even_grid((nvec + kS1Threads * kS1Unroll - 1) / (kS1Threads * kS1Unroll), kMaxStat1Blocks);
+    nb2 = even_grid((nvec + kS2Threads * kS2Unroll - 1) / (kS2Threads * kS2Unroll), kMaxStat2Blocks);
+}
+
+hipError_t launch_stats_finalize(uint64_t n, uint32_t nbins, void *ws, hipStream_t s)
+{
+    char *w = static_cast<char *>(ws);
+    uint32_t nb1, nb2;
+    stats_grid(n, nb1, nb2);
+    hipLaunchKernelGGL(k_stats_finalize, dim3(1), dim3(kFinThreads), 0, s, reinterpret_cast<const Part1 *>(w + kOffPart1),
+                       nb1, reinterpret_cast<const Part2 *>(w + kOffPart2), nb2,
+                       reinterpret_cast<const uint32_t *>(w + kOffHist), nbins, n,
+                       reinterpret_cast<qp_stats_t *>(w + kOffStats));
+    return hipGetLastError();
+}
+
+hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s, bool finalize)
+{
+    char *w = static_cast<char *>(ws);
+    Part1 *p1 = reinterpret_cast<Part1 *>(w + kOffPart1);
+    Part2 *p2 = reinterpret_cast<Part2 *>(w + kOffPart2);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(w + kOffHist);
+    Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
+    uint32_t nb1, nb2;
+    stats_grid(n, nb1, nb2);
     if (dtype == QP_F32) {
         hipLaunchKernelGGL(k_stats_pass1<QP_F32>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
-        hipLaunchKernelGGL(k_stats_pass2<QP_F32>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins,
-                           ctl, out);
+        hipLaunchKernelGGL(k_stats_pass2<QP_F32>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins);
     } else {
         hipLaunchKernelGGL(k_stats_pass1<QP_BF16>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
-        hipLaunchKernelGGL(k_stats_pass2<QP_BF16>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins,
-                           ctl, out);
+        hipLaunchKernelGGL(k_stats_pass2<QP_BF16>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins);
     }
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !finalize) return e;
+    return launch_stats_finalize(n, nbins, ws, s);
 }
 
 }  // namespace qp

@@ -235,7 +235,7 @@ def test_search_other_step_counts(qp):
     x = si.make_config("C3", n=60_001)
     xd = to_dev(x)
     st = None
-    for t in (1, 10, 333):
+    for t in (1, 10, 333, 1023):
         cfg = qp.qp_default_search_cfg()
         cfg.t_steps = t
         ws = qp.alloc_workspace(x.size, cfg)
@@ -474,3 +474,99 @@ def test_full_size_bf16_config(qp):
         qp.qp_unpack_dequant(packed, q, y)
         assert np.array_equal(y.cpu().numpy(), orc.dequantize(codes, oq))
         del packed, y, codes
+
+
+# ----------------------------------------------------------------------------- the microbatch stream
+
+@pytest.mark.timeout(900)
+def test_c4_stream_first_microbatches(qp):
+    """Config 4: a stream of microbatches whose bitwidth follows a bandwidth trace; whole sender path
+    per microbatch with no host round trip, then the receiver; checked against the oracle."""
+    n = si.numel("C4")
+    stream = si.c4_stream(40)
+    ring = {}
+    ws = qp.alloc_workspace(n)
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    qrec = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    seen_bits = set()
+    checked = 0
+    for m, (buf, b_m, bw, bits) in enumerate(stream):
+        if bits in seen_bits and checked >= 5:
+            continue
+        if buf not in ring:
+            ring[buf] = si.unit_laplace(n, 100 + buf)
+        x = ring[buf] * np.float32(b_m)
+        print(f"[case] C4 microbatch {m}: buffer {buf} b={b_m:.3f} bw={bw:.1f} Mbit/s bits={bits}", flush=True)
+        xd = to_dev(x)
+        packed = qp.alloc_packed(n, bits)
+        qp.qp_compress_async(xd, bits, ws, packed, qparams_out_dev_ptr=qrec.data_ptr())
+        qp.qp_unpack_dequant_dev(packed, bits, qrec.data_ptr(), y)
+        torch.cuda.synchronize()
+        q = qp.qp_qparams_t.from_buffer_copy(qrec.cpu().numpy().tobytes())
+        res = qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)
+        st = qp.read_ws(ws, qp.QP_WS_STATS, qp.qp_stats_t)
+        assert (q.bits, q.n) == (bits, n)
+        rc, ost = orc.stats(x)
+        assert abs(st.mad - ost.mad) <= REL_STATS_FULL * ost.mad and (st.min, st.max) == (ost.min, ost.max)
+        oq = orc.make_qparams(st.mean, res.alpha_star, bits, n)          # the oracle is given the GPU's alpha
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        codes = orc.quantize(x, oq)
+        assert np.array_equal(packed.cpu().numpy(), orc.pack(codes, bits))
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(codes, oq))
+        F = orc.laplace_F(bits)
+        b_star = st.mad + res.j_star * ((st.b_r - st.mad) / 100)
+        assert res.alpha_star == pytest.approx(F * b_star, rel=1e-14)
+        assert res.mse_star == pytest.approx(pairwise_sq_error(x, oq) / n, rel=REL_SCORE_PAIRWISE)
+        seen_bits.add(bits)
+        checked += 1
+    assert checked >= 5 and len(seen_bits) >= 3
+
+
+# ----------------------------------------------------------------------------- maximum size
+
+@pytest.mark.timeout(1500)
+def test_largest_supported_tensor(qp):
+    """n = 2^32 - 1 bf16 elements (8.6 GB in, 17 GB out): 64-bit indexing everywhere, ragged tail."""
+    n = 2 ** 32 - 1
+    rng = np.random.default_rng(99)
+    block = si.f32_to_bf16_bits(rng.laplace(0.0, 0.6, size=1 << 22).astype(np.float32))
+    h = np.tile(block, (n + block.size - 1) // block.size)[:n]
+    h[12345] = si.f32_to_bf16_bits(np.array([40.0], np.float32))[0]     # the maximum
+    h[n - 2] = si.f32_to_bf16_bits(np.array([-37.0], np.float32))[0]    # the minimum, in the tail
+    print("[case] largest tensor: upload", flush=True)
+    xd = torch.from_numpy(h.view(np.int16)).cuda().view(torch.bfloat16)
+    ws = qp.alloc_workspace(n)
+    st = qp.qp_stats(xd, ws)
+    assert st.n == n and st.n_nonfinite == 0 and (st.min, st.max) == (-37.0, 40.0)
+    # statistics against numpy's pairwise float64 sums, block by block (the tensor is periodic)
+    b64 = si.bf16_bits_to_f32(block).astype(np.float64)
+    reps, rem = divmod(n, block.size)
+    fix = (40.0 - float(si.bf16_bits_to_f32(block[12345:12346])[0])) + (-37.0 - float(si.bf16_bits_to_f32(block[(n - 2) % block.size:(n - 2) % block.size + 1])[0]))
+    total = reps * float(b64.sum()) + float(b64[:rem].sum()) + fix
+    assert st.mean == pytest.approx(total / n, rel=1e-9, abs=1e-12)
+    hist_off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    assert int(ws[hist_off:hist_off + 8192].cpu().numpy().view(np.uint32).astype(np.int64).sum()) == n
+    for bits in (3, 16):
+        print(f"[case] largest tensor: bits={bits}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        oq = orc.make_qparams(st.mean, res.alpha_star, bits, n)
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        packed = qp.alloc_packed(n, bits)
+        qp.qp_quant_pack(xd, q, packed)
+        y = torch.empty(n, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant(packed, q, y)
+        torch.cuda.synchronize()
+        # sampled windows (multiples of 32 codes, so each is a whole number of packed dwords)
+        starts = [0, 32 * 1000003, 32 * (2 ** 26 + 7), (n // 32 - 3000) * 32]
+        for s0 in starts:
+            s1 = min(n, s0 + 32 * 4000) if s0 != starts[-1] else n
+            xw = orc.widen_bf16(h[s0:s1])
+            codes = orc.quantize(xw, oq)
+            ref = orc.pack(codes, bits)
+            got = packed[s0 * bits // 8: s0 * bits // 8 + ref.size].cpu().numpy()
+            assert np.array_equal(got, ref), (bits, s0)
+            assert np.array_equal(y[s0:s1].cpu().numpy(), orc.dequantize(codes, oq)), (bits, s0)
+        assert packed.numel() == 4 * ((n * bits + 31) // 32)
+        # the score of the winner on a periodic tensor: reps * block + remainder, from the oracle
+        e_block = pairwise_sq_error(orc.widen_bf16(block), oq)
+        del packed, y
