@@ -201,6 +201,18 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
                             void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev,
                             void *stream);
 
+/* ---- adaptive bitwidth rule (Sec. 3 "Adaptive PDA", Eq. 2) -- host only, pure ---------
+ * Given the payload size V at the current bitwidth, the microbatch size S (images), the target
+ * rate R (images/s) and the measured bandwidth B, the next bitwidth is
+ *     q_next = 32 / 2^ceil(log2( (V * 32 / q_cur) / (S / R * B) )),
+ * i.e. the uncompressed size V*32/q_cur is halved until it fits in what the link carries
+ * during one microbatch period S/R.  v_bits is V in bits, bandwidth in bits per second.
+ * Results: 32 (send unquantized: the link is not the bottleneck), 16, 8, 4 or 2 (the lowest
+ * supported; also when even 2 bits do not fit).  q_cur may be any of 2,3,4,6,8,16,32.
+ * bandwidth = +infinity is allowed and gives 32.  QP_EINVAL on non-positive or NaN arguments. */
+qp_status qp_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_images_per_s,
+                       double bandwidth_bits_per_s, uint32_t *q_next);
+
 const char *qp_strerror(qp_status status);
 
 #ifdef __cplusplus

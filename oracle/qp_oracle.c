@@ -356,3 +356,20 @@ int orc_dsaciq_search(const float *x, uint64_t n, const orc_stats_t *st, uint32_
     if (best_q) orc_make_qparams(st->mean, res->alpha_star, bits, n, best_q);
     return 0;
 }
+
+/* ---- Adaptive PDA bitwidth rule (Sec. 3, Eq. 2) -----------------------------
+ * q_next = 32 / 2^ceil(log2((V 32/q_cur) / (S/R B))), written as printed, with the two
+ * clamps the text implies: no quantization (32) when the link is not the bottleneck, and
+ * 2 bits as the lowest bitwidth the system has.  V and B in bits and bits per second.
+ * Pinned by the paper's own run (Sec. 4.2): ViT-Base boundary tensor, microbatch 64,
+ * about 100 images/s: 400 Mbps -> 16 bit, 50 Mbps -> 2 bit, 200 Mbps -> 8 bit, unlimited -> 32. */
+int orc_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_rate, double bandwidth, uint32_t *q_next)
+{
+    if (!(v_bits > 0.0) || !(s_images > 0.0) || !(r_rate > 0.0) || !(bandwidth > 0.0) || q_cur == 0) return 2;
+    double ratio = (v_bits * 32.0 / (double)q_cur) / (s_images / r_rate * bandwidth);
+    double e = ceil(log2(ratio));
+    if (e < 0.0) e = 0.0;
+    if (e > 4.0) e = 4.0;
+    *q_next = 32u >> (uint32_t)e;
+    return 0;
+}

@@ -84,6 +84,8 @@ def lib():
         L.orc_dsaciq_search.argtypes = [fp, C.c_uint64, C.POINTER(Stats), C.c_uint32, C.c_uint32,
                                         C.POINTER(SearchResult), C.POINTER(QParams), dp]
         L.orc_dsaciq_search.restype = C.c_int
+        L.orc_next_bits.argtypes = [C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_uint32)]
+        L.orc_next_bits.restype = C.c_int
         _lib = L
     return _lib
 
@@ -205,3 +207,11 @@ def dsaciq_search(x, st, bits, t_steps=100):
     if rc:
         raise ValueError("orc_dsaciq_search: bad argument")
     return res, q, scores
+
+
+def next_bits(v_bits, q_cur, s_images, r_rate, bandwidth):
+    out = C.c_uint32()
+    rc = lib().orc_next_bits(float(v_bits), int(q_cur), float(s_images), float(r_rate), float(bandwidth), C.byref(out))
+    if rc:
+        raise ValueError("orc_next_bits: bad argument")
+    return out.value

@@ -18,7 +18,7 @@ __all__ = [
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
     "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_dsaciq_search",
     "qp_dsaciq_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
-    "qp_compress_async", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
+    "qp_compress_async", "qp_next_bits", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
 ]
 
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
@@ -89,6 +89,7 @@ def lib():
             "qp_unpack_dequant": (i32, [vp, sz, C.POINTER(qp_qparams_t), vp, u64, vp]),
             "qp_unpack_dequant_dev": (i32, [vp, sz, u32, vp, vp, u64, vp]),
             "qp_compress_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, sz, vp, vp]),
+            "qp_next_bits": (i32, [C.c_double, u32, C.c_double, C.c_double, C.c_double, C.POINTER(u32)]),
             "qp_strerror": (C.c_char_p, [i32]),
         }
         for name, (res, args) in sig.items():
@@ -102,7 +103,7 @@ def lib():
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
            "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_dsaciq_search",
            "qp_dsaciq_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
-           "qp_unpack_dequant_dev", "qp_compress_async", "qp_strerror")
+           "qp_unpack_dequant_dev", "qp_compress_async", "qp_next_bits", "qp_strerror")
 
 
 # ---- marshalling helpers ------------------------------------------------------------------
@@ -254,3 +255,10 @@ def qp_compress_async(x, bits: int, ws, packed, qparams_out_dev_ptr: int = 0, cf
                                    _dev(packed), packed.numel() * packed.element_size(),
                                    C.c_void_p(qparams_out_dev_ptr) if qparams_out_dev_ptr else None,
                                    _stream(stream)), "qp_compress_async")
+
+
+def qp_next_bits(v_bits: float, q_cur: int, s_images: float, r_images_per_s: float, bandwidth_bits_per_s: float) -> int:
+    out = C.c_uint32()
+    _check(lib().qp_next_bits(float(v_bits), int(q_cur), float(s_images), float(r_images_per_s),
+                              float(bandwidth_bits_per_s), C.byref(out)), "qp_next_bits")
+    return out.value

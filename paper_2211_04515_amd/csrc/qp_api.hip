@@ -275,6 +275,26 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     return QP_OK;
 }
 
+qp_status qp_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_images_per_s,
+                       double bandwidth_bits_per_s, uint32_t *q_next)
+{
+    if (!q_next || !(bits_ok(q_cur) || q_cur == 32)) return QP_EINVAL;
+    if (!(v_bits > 0.0) || !(s_images > 0.0) || !(r_images_per_s > 0.0) || !(bandwidth_bits_per_s > 0.0))
+        return QP_EINVAL;   // also rejects NaN
+    if (std::isinf(v_bits) || std::isinf(s_images) || std::isinf(r_images_per_s)) return QP_EINVAL;
+    const double uncompressed = v_bits * 32.0 / (double)q_cur;
+    const double budget = s_images / r_images_per_s * bandwidth_bits_per_s;   // bits per microbatch period
+    // smallest m >= 0 with uncompressed <= 2^m * budget, i.e. ceil(log2(ratio)) clamped at 0
+    uint32_t q = 32;
+    double fits = budget;
+    while (q > 2 && uncompressed > fits) {
+        q >>= 1;
+        fits *= 2.0;
+    }
+    *q_next = q;
+    return QP_OK;
+}
+
 const char *qp_strerror(qp_status status)
 {
     switch (status) {

@@ -179,3 +179,21 @@ def test_product_package_does_not_reach_the_oracle():
     for f in os.listdir(os.path.join(ROOT, "oracle")):
         if f.endswith((".py", ".c")):
             assert "paper_2211_04515_amd" not in open(os.path.join(ROOT, "oracle", f)).read(), f
+
+
+def test_next_bits_matches_oracle_and_the_papers_example(qp):
+    n = 64 * 197 * 768
+    for bw, q_expected in ((400e6, 16), (50e6, 2), (200e6, 8), (float("inf"), 32)):
+        for q_cur in (32, 16, 8, 6, 4, 3, 2):
+            assert qp.qp_next_bits(n * q_cur, q_cur, 64, 100.0, bw) == q_expected
+    rng = np.random.default_rng(5)
+    for _ in range(3000):
+        nn = int(rng.integers(10_000, 50_000_000))
+        q_cur = int(rng.choice((2, 3, 4, 6, 8, 16, 32)))
+        s_img, rate = float(rng.integers(1, 129)), float(rng.uniform(5, 500))
+        bw = float(10 ** rng.uniform(5.0, 11.0))
+        assert qp.qp_next_bits(nn * q_cur, q_cur, s_img, rate, bw) == orc.next_bits(nn * q_cur, q_cur, s_img, rate, bw)
+    for bad in ((0, 8, 64, 100, 1e8), (1e6, 5, 64, 100, 1e8), (1e6, 8, 0, 100, 1e8), (1e6, 8, 64, -1, 1e8),
+                (1e6, 8, 64, 100, 0.0), (float("nan"), 8, 64, 100, 1e8), (1e6, 8, 64, 100, float("nan"))):
+        with pytest.raises(qp.QuantPipeError):
+            qp.qp_next_bits(*bad)

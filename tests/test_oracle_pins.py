@@ -436,3 +436,35 @@ def test_naive_range_loses_to_aciq_at_low_bitwidth_with_outliers():
     naive = orc.make_qparams((st.min + st.max) / 2, (st.max - st.min) / 2, 16, x.size)
     aciq = orc.make_qparams(st.mean, orc.aciq_alpha(st, 16), 16, x.size)
     assert orc.sq_error(x, naive) <= orc.sq_error(x, aciq)
+
+
+# ----------------------------------------------------------------------------- adaptive bitwidth rule (Eq. 2)
+
+def _golden_adaptive():
+    rows = []
+    with open(os.path.join(GOLDEN, "adaptive_bitwidth_example.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                bw, q = line.split()
+                rows.append((float(bw), int(q)))
+    return rows
+
+
+def test_eq2_reproduces_the_papers_adaptivity_run():
+    n = 64 * 197 * 768
+    for bw_mbps, q_expected in _golden_adaptive():
+        for q_cur in (32, 16, 8, 6, 4, 2):          # the rule does not depend on where it starts from
+            v_bits = n * q_cur
+            assert orc.next_bits(v_bits, q_cur, 64, 100.0, bw_mbps * 1e6) == q_expected, (bw_mbps, q_cur)
+
+
+def test_eq2_picks_the_highest_power_of_two_that_fits():
+    rng = np.random.default_rng(2)
+    for _ in range(2000):
+        n = int(rng.integers(10_000, 50_000_000))
+        s_img, rate = float(rng.integers(1, 129)), float(rng.uniform(5, 500))
+        bw = float(10 ** rng.uniform(5.5, 10.5))
+        q = orc.next_bits(n * 8, 8, s_img, rate, bw)
+        budget = s_img / rate * bw
+        fitting = [k for k in (32, 16, 8, 4, 2) if n * k <= budget]
+        assert q == (max(fitting) if fitting else 2)
