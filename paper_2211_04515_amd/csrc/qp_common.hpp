@@ -117,6 +117,47 @@ template <> struct Vec4<QP_BF16> {
     }
 };
 
+// ---- 16-byte loads for the streaming reductions: 4 fp32 or 8 bf16 elements per lane -------
+template <int DT> struct Vec16;
+template <> struct Vec16<QP_F32> {
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ void load(const void *base, uint64_t vec, float (&f)[4])
+    {
+        const float4 v = reinterpret_cast<const float4 *>(base)[vec];
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+};
+template <> struct Vec16<QP_BF16> {
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ void load(const void *base, uint64_t vec, float (&f)[8])
+    {
+        const uint4 v = reinterpret_cast<const uint4 *>(base)[vec];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+// the same 16-byte load, nontemporal: for data a kernel touches exactly once
+template <int DT> __device__ __forceinline__ void load16_stream(const void *base, uint64_t vec, float (&f)[Vec16<DT>::kElems])
+{
+    if constexpr (DT == QP_F32) {
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(base) + vec);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    } else {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base) + vec);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+}
+
 // ---- "last block finishes" tickets ---------------------------------------------------
 // A block publishes its partial results with a device-scope RELEASE on the ticket counter; only
 // the block that draws the last ticket pays for the ACQUIRE (cache invalidation) before it
@@ -351,14 +392,14 @@ inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b 
 // The two streaming passes of the statistics; `finalize` adds the one-block kernel that turns the
 // partials into the qp_stats_t record (left out when the search set-up kernel will do it).
 hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s, bool finalize);
-void stats_grid(uint64_t n, uint32_t &nb1, uint32_t &nb2);
+void stats_grid(uint64_t n, int dtype, uint32_t &nb1, uint32_t &nb2);
 // Set-up + search.  stats_host_or_null: statistics from the host, else they are taken from the
 // workspace; finalize_nbins != 0: the set-up kernel first finalizes the statistics that
 // launch_stats(..., finalize = false) left as partials (histogram of finalize_nbins bins).
 hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
                          double F, const qp_stats_t *stats_host_or_null, uint32_t finalize_nbins, void *ws,
                          hipStream_t s);
-hipError_t launch_stats_finalize(uint64_t n, uint32_t nbins, void *ws, hipStream_t s);
+hipError_t launch_stats_finalize(uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s);
 uint32_t search_blocks(uint64_t n);
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *host_qp,
                              const qp_qparams_t *dev_qp, void *packed, hipStream_t s);

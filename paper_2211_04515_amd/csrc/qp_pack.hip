@@ -1,11 +1,12 @@
 // Step 3: clip + uniform quantize + bit-pack (Sec. 3: ACIQ clipping, then PTQ with the
 // chosen bitwidth).  HBM-bound: (4 + k/8) bytes per fp32 element, (2 + k/8) per bf16.
 //
-// One block of 256 lanes (four wave64s) owns a tile of 4096 consecutive elements.
+// One block of 256 lanes (four wave64s) owns a tile of 4096 (fp32) or 8192 (bf16) consecutive
+// elements, 16 KB of input either way.
 //   stage 1  each lane issues four coalesced 16-byte loads (lane i of a wave reads bytes
-//            [16 i, 16 i + 16) of a 1 KB segment), quantizes the four elements of each load
-//            and merges their codes into one 4k-bit chunk, which it writes to LDS at the
-//            chunk's position in the tile;
+//            [16 i, 16 i + 16) of a 1 KB segment), quantizes the elements of each load and
+//            merges the codes of four neighbours into one 4k-bit chunk, which it writes to LDS
+//            at the chunk's position in the tile;
 //   stage 2  the LDS tile is (k = 2,4,8,16) already the output byte stream, or (k = 3,6) an
 //            array of 12/24-bit chunks that eight/four at a time squeeze into three dwords;
 //            lanes read it back 16 bytes at a time and store 128-bit (k = 3,6: 96-bit)
@@ -19,16 +20,20 @@
 namespace qp {
 
 constexpr int kPkThreads = 256;
-constexpr int kPkLoads = 4;                               // 4-element vectors per lane
-constexpr int kPkChunks = kPkThreads * kPkLoads;          // 1024 chunks of 4 codes
-constexpr int kPkTile = kPkChunks * 4;                    // 4096 elements
+constexpr int kPkLoads = 4;                               // 16-byte loads per lane
+// a load brings 4 fp32 or 8 bf16 elements, i.e. one or two chunks of 4 codes
+template <int DT> struct PackTile {
+    static constexpr int chunks_per_load = Vec16<DT>::kElems / 4;
+    static constexpr int chunks = kPkThreads * kPkLoads * chunks_per_load;   // 1024 (fp32) / 2048 (bf16)
+    static constexpr int elems = chunks * 4;                                  // 4096 / 8192 elements per tile
+};
 
 struct Grid4 {
     float lo, hi, inv_scale, L;
 };
 
-template <int K> struct PackLds {           // bytes of LDS per tile
-    static constexpr int bytes = kPkChunks * ((K == 2) ? 1 : (K == 3 || K == 4) ? 2 : (K == 6 || K == 8) ? 4 : 8);
+template <int K> struct PackLds {           // bytes of LDS per chunk
+    static constexpr int per_chunk = (K == 2) ? 1 : (K == 3 || K == 4) ? 2 : (K == 6 || K == 8) ? 4 : 8;
 };
 
 // merge four codes (floats holding integers in [0, 2^K - 1]) and put the chunk in LDS
@@ -59,7 +64,10 @@ __global__ __launch_bounds__(kPkThreads) void k_quant_pack(const void *__restric
                                                            const qp_qparams_t *__restrict__ qdev,
                                                            uint32_t *__restrict__ out, uint64_t ndw)
 {
-    __shared__ __align__(16) unsigned char lds[PackLds<K>::bytes];
+    constexpr int kPkTile = PackTile<DT>::elems;
+    constexpr int CPL = PackTile<DT>::chunks_per_load;
+    constexpr int E = Vec16<DT>::kElems;
+    __shared__ __align__(16) unsigned char lds[PackTile<DT>::chunks * PackLds<K>::per_chunk];
     const uint32_t tid = threadIdx.x;
     if (qdev) {   // grid left in device memory by the search
         g.lo = qdev->lo;
@@ -70,21 +78,23 @@ __global__ __launch_bounds__(kPkThreads) void k_quant_pack(const void *__restric
 
     // ---- stage 1 ----
     if (e0 + kPkTile <= n) {
-        float f[kPkLoads][4];
+        float f[kPkLoads][E];
+#pragma unroll
+        for (int u = 0; u < kPkLoads; ++u)
+            load16_stream<DT>(x, e0 / E + (uint64_t)u * kPkThreads + tid, f[u]);
 #pragma unroll
         for (int u = 0; u < kPkLoads; ++u) {
-            Vec4<DT>::load_stream(x, e0 / 4 + (uint64_t)u * kPkThreads + tid, f[u]);
-        }
 #pragma unroll
-        for (int u = 0; u < kPkLoads; ++u) {
-            float r[4];
+            for (int h = 0; h < CPL; ++h) {
+                float r[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = quant_level(f[u][i], g.lo, g.hi, g.inv_scale, g.L);
-            put_chunk<K>(lds, (uint32_t)u * kPkThreads + tid, r);
+                for (int i = 0; i < 4; ++i) r[i] = quant_level(f[u][4 * h + i], g.lo, g.hi, g.inv_scale, g.L);
+                put_chunk<K>(lds, ((uint32_t)u * kPkThreads + tid) * CPL + h, r);
+            }
         }
     } else {   // last, partial tile: elements past the end count as code 0
 #pragma unroll 1
-        for (int u = 0; u < kPkLoads; ++u) {
+        for (int u = 0; u < kPkLoads * CPL; ++u) {
             const uint32_t ci = (uint32_t)u * kPkThreads + tid;
             const uint64_t e = e0 + 4ull * ci;
             float r[4];
@@ -147,13 +157,15 @@ static hipError_t launch_k(const void *x, uint64_t n, int dtype, Grid4 g, const 
                            hipStream_t s)
 {
     const uint64_t ndw = (n * K + 31) / 32;
-    const uint32_t blocks = ceil_div_u64(n, kPkTile);
-    if (dtype == QP_F32)
+    if (dtype == QP_F32) {
+        const uint32_t blocks = ceil_div_u64(n, PackTile<QP_F32>::elems);
         hipLaunchKernelGGL((k_quant_pack<K, QP_F32>), dim3(blocks), dim3(kPkThreads), 0, s, x, n, g, qdev,
                            static_cast<uint32_t *>(packed), ndw);
-    else
+    } else {
+        const uint32_t blocks = ceil_div_u64(n, PackTile<QP_BF16>::elems);
         hipLaunchKernelGGL((k_quant_pack<K, QP_BF16>), dim3(blocks), dim3(kPkThreads), 0, s, x, n, g, qdev,
                            static_cast<uint32_t *>(packed), ndw);
+    }
     return hipGetLastError();
 }
 

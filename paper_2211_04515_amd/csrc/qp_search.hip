@@ -348,7 +348,7 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
 
     FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                      reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
-    if (finalize_nbins) stats_grid(n, fin.nb1, fin.nb2);
+    if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, stats_dev, st ? st->mean : 0.0,
                        st ? st->mad : 0.0, st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets,
                        fin);

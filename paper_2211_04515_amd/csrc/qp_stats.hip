@@ -1,7 +1,8 @@
 // Step 1: per-tensor statistics and histogram (Sec. 3: mu and b of L(mu, b); the
 // estimate b_E; the histogram D_R of the real data; the bound b_R from its peak).
 //
-// Two streaming passes, both HBM-bound (4 B per fp32 element each):
+// Two streaming passes, both HBM-bound (4 B per fp32 element each), 16-byte loads (4 fp32 or 8
+// bf16 elements per lane):
 //   pass 1  sum, sum|x|, min, max, NaN/Inf count        -> one partial per block
 //   pass 2  sum|x - mu|, sum (x - mu)^2, histogram      -> partial per block + LDS histogram
 // Accumulation is fp64 per lane, reduced inside each wave64 with DPP lane permutations, one
@@ -20,6 +21,14 @@ constexpr int kS1Threads = 256;
 constexpr int kS1Unroll = 4;     // 16-byte loads in flight per lane
 constexpr int kS2Threads = 512;
 constexpr int kS2Unroll = 4;
+constexpr uint32_t kHistWords = 16384;   // 64 KB of LDS: two blocks of pass 2 per CU
+// copies of the LDS histogram: as many as fit, at most 8 (2048 bins -> 8, 4096 -> 4)
+inline uint32_t hist_rep_shift(uint32_t nbins)
+{
+    uint32_t s = 0;
+    while (s < 3 && (nbins << (s + 1)) <= kHistWords) ++s;
+    return s;
+}
 
 struct Acc1 {
     double s, sa;
@@ -51,35 +60,38 @@ __global__ __launch_bounds__(kS1Threads) void k_stats_pass1(const void *__restri
 
     Acc1 a0{0.0, 0.0, INFINITY, -INFINITY, 0u};
     Acc1 a1 = a0;
-    const uint64_t nvec = n / 4;
+    constexpr int E = Vec16<DT>::kElems;   // elements per 16-byte load
+    const uint64_t nvec = n / E;
     const uint64_t tile = (uint64_t)kS1Threads * kS1Unroll;
     uint64_t base = (uint64_t)blockIdx.x * tile;
     const uint64_t stride = (uint64_t)gridDim.x * tile;
     for (; base + tile <= nvec; base += stride) {
-        float f[kS1Unroll][4];
+        float f[kS1Unroll][E];
 #pragma unroll
-        for (int u = 0; u < kS1Unroll; ++u) Vec4<DT>::load(x, base + (uint64_t)u * kS1Threads + tid, f[u]);
+        for (int u = 0; u < kS1Unroll; ++u) Vec16<DT>::load(x, base + (uint64_t)u * kS1Threads + tid, f[u]);
 #pragma unroll
         for (int u = 0; u < kS1Unroll; ++u) {
-            acc1_add(a0, f[u][0]);
-            acc1_add(a1, f[u][1]);
-            acc1_add(a0, f[u][2]);
-            acc1_add(a1, f[u][3]);
+#pragma unroll
+            for (int e = 0; e < E; e += 2) {
+                acc1_add(a0, f[u][e]);
+                acc1_add(a1, f[u][e + 1]);
+            }
         }
     }
     // the block whose turn it is takes the ragged remainder of whole vectors
     if (base < nvec) {
         for (uint64_t v = base + tid; v < nvec; v += kS1Threads) {
-            float f[4];
-            Vec4<DT>::load(x, v, f);
-            acc1_add(a0, f[0]);
-            acc1_add(a1, f[1]);
-            acc1_add(a0, f[2]);
-            acc1_add(a1, f[3]);
+            float f[E];
+            Vec16<DT>::load(x, v, f);
+#pragma unroll
+            for (int e = 0; e < E; e += 2) {
+                acc1_add(a0, f[e]);
+                acc1_add(a1, f[e + 1]);
+            }
         }
     }
-    // last n mod 4 elements
-    if (blockIdx.x == 0 && tid < (uint32_t)(n - nvec * 4)) acc1_add(a0, Vec4<DT>::load1(x, nvec * 4 + tid));
+    // last n mod E elements
+    if (blockIdx.x == 0 && tid < (uint32_t)(n - nvec * E)) acc1_add(a0, Vec4<DT>::load1(x, nvec * E + tid));
 
     double s = wave_sum(a0.s + a1.s);
     double sa = wave_sum(a0.sa + a1.sa);
@@ -104,31 +116,39 @@ __global__ __launch_bounds__(kS1Threads) void k_stats_pass1(const void *__restri
     }
 }
 
-template <int DT>
+// REP_SHIFT: log2 of the number of LDS histogram copies (compile-time so that the address is one
+// shift-add).
+template <int DT, int REP_SHIFT>
 __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restrict__ x, uint64_t n,
                                                             const Part1 *__restrict__ part1, uint32_t nb1,
                                                             Part2 *__restrict__ part2, uint32_t *__restrict__ hist,
                                                             uint32_t nbins)
 {
-    __shared__ uint32_t sh_hist[kMaxBins];
+    // The LDS histogram is kept in `rep` interleaved copies (copy = lane mod rep): lanes that hit the
+    // same bin then update different addresses in different banks, which divides the serialisation
+    // of LDS atomics on peaked data (most of the mass in a few bins) by rep.
+    __shared__ uint32_t sh_hist[kHistWords];
     __shared__ Part1 sh1[kS2Threads / kWave];
     __shared__ Part2 sh2[kS2Threads / kWave];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid / kWave, lane = tid % kWave;
 
-    for (uint32_t b = tid; b < nbins; b += kS2Threads) sh_hist[b] = 0u;
+    constexpr uint32_t rep_shift = REP_SHIFT;
+    const uint32_t copy = tid & ((1u << rep_shift) - 1u);
+    for (uint32_t b = tid; b < (nbins << rep_shift); b += kS2Threads) sh_hist[b] = 0u;
 
     // the block's first tile is requested before anything else, so that the tensor is already
     // streaming while the pass-1 partials are being reduced
-    const uint64_t nvec = n / 4;
+    constexpr int E = Vec16<DT>::kElems;   // elements per 16-byte load
+    const uint64_t nvec = n / E;
     const uint64_t tile = (uint64_t)kS2Threads * kS2Unroll;
     uint64_t base = (uint64_t)blockIdx.x * tile;
     const uint64_t stride = (uint64_t)gridDim.x * tile;
-    float pre[kS2Unroll][4];
+    float pre[kS2Unroll][E];
     const bool have_pre = base + tile <= nvec;
     if (have_pre) {
 #pragma unroll
-        for (int u = 0; u < kS2Unroll; ++u) Vec4<DT>::load(x, base + (uint64_t)u * kS2Threads + tid, pre[u]);
+        for (int u = 0; u < kS2Unroll; ++u) Vec16<DT>::load(x, base + (uint64_t)u * kS2Threads + tid, pre[u]);
     }
 
     // ---- every block reduces the pass-1 partials in the same fixed order ----
@@ -149,49 +169,54 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
         dev += fabs(d);
         sq = fma(d, d, sq);
         const float tt = (v - mn) * w_inv;
-        const uint32_t idx = (uint32_t)fminf(fmaxf(tt, 0.0f), top);   // NaN (0*inf) -> 0
-        atomicAdd(&sh_hist[idx], 1u);
+        // clamp to [0, nbins-1] in one operation; a NaN (0*inf when min == max) gives 0
+        const uint32_t idx = (uint32_t)__builtin_amdgcn_fmed3f(tt, 0.0f, top);
+        atomicAdd(&sh_hist[(idx << rep_shift) + copy], 1u);
     };
     if (have_pre) {
 #pragma unroll
         for (int u = 0; u < kS2Unroll; ++u) {
-            add(pre[u][0], dev0, sq0);
-            add(pre[u][1], dev1, sq1);
-            add(pre[u][2], dev0, sq0);
-            add(pre[u][3], dev1, sq1);
+#pragma unroll
+            for (int e = 0; e < E; e += 2) {
+                add(pre[u][e], dev0, sq0);
+                add(pre[u][e + 1], dev1, sq1);
+            }
         }
         base += stride;
     }
     for (; base + tile <= nvec; base += stride) {
-        float f[kS2Unroll][4];
+        float f[kS2Unroll][E];
 #pragma unroll
-        for (int u = 0; u < kS2Unroll; ++u) Vec4<DT>::load(x, base + (uint64_t)u * kS2Threads + tid, f[u]);
+        for (int u = 0; u < kS2Unroll; ++u) Vec16<DT>::load(x, base + (uint64_t)u * kS2Threads + tid, f[u]);
 #pragma unroll
         for (int u = 0; u < kS2Unroll; ++u) {
-            add(f[u][0], dev0, sq0);
-            add(f[u][1], dev1, sq1);
-            add(f[u][2], dev0, sq0);
-            add(f[u][3], dev1, sq1);
+#pragma unroll
+            for (int e = 0; e < E; e += 2) {
+                add(f[u][e], dev0, sq0);
+                add(f[u][e + 1], dev1, sq1);
+            }
         }
     }
     if (base < nvec) {
         for (uint64_t v = base + tid; v < nvec; v += kS2Threads) {
-            float f[4];
-            Vec4<DT>::load(x, v, f);
-            add(f[0], dev0, sq0);
-            add(f[1], dev1, sq1);
-            add(f[2], dev0, sq0);
-            add(f[3], dev1, sq1);
+            float f[E];
+            Vec16<DT>::load(x, v, f);
+#pragma unroll
+            for (int e = 0; e < E; e += 2) {
+                add(f[e], dev0, sq0);
+                add(f[e + 1], dev1, sq1);
+            }
         }
     }
-    if (blockIdx.x == 0 && tid < (uint32_t)(n - nvec * 4)) add(Vec4<DT>::load1(x, nvec * 4 + tid), dev0, sq0);
+    if (blockIdx.x == 0 && tid < (uint32_t)(n - nvec * E)) add(Vec4<DT>::load1(x, nvec * E + tid), dev0, sq0);
 
     const double dev = wave_sum(dev0 + dev1);
     const double sq = wave_sum(sq0 + sq1);
     if (lane == 0) sh2[wave] = Part2{dev, sq};
     __syncthreads();   // also orders the LDS histogram updates before the merge below
     for (uint32_t b = tid; b < nbins; b += kS2Threads) {
-        const uint32_t c = sh_hist[b];
+        uint32_t c = 0u;
+        for (uint32_t r = 0; r < (1u << rep_shift); ++r) c += sh_hist[(b << rep_shift) + r];
         if (c) atomicAdd(&hist[b], c);
     }
     if (tid == 0) {
@@ -214,9 +239,9 @@ __global__ __launch_bounds__(kFinThreads) void k_stats_finalize(const Part1 *__r
 
 // Whole tiles per block: with T tiles and at most B blocks, every block takes ceil(T/B) tiles and
 // the grid shrinks to the number of blocks that this needs.
-void stats_grid(uint64_t n, uint32_t &nb1, uint32_t &nb2)
+void stats_grid(uint64_t n, int dtype, uint32_t &nb1, uint32_t &nb2)
 {
-    const uint64_t nvec = n / 4;
+    const uint64_t nvec = n / (dtype == QP_BF16 ? 8 : 4);   // 16-byte vectors
     auto even_grid = [](uint64_t tiles, uint32_t max_blocks) -> uint32_t {
         if (tiles < 1) return 1u;
         const uint64_t per = (tiles + max_blocks - 1) / max_blocks;
@@ -226,11 +251,11 @@ void stats_grid(uint64_t n, uint32_t &nb1, uint32_t &nb2)
     nb2 = even_grid((nvec + kS2Threads * kS2Unroll - 1) / (kS2Threads * kS2Unroll), kMaxStat2Blocks);
 }
 
-hipError_t launch_stats_finalize(uint64_t n, uint32_t nbins, void *ws, hipStream_t s)
+hipError_t launch_stats_finalize(uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s)
 {
     char *w = static_cast<char *>(ws);
     uint32_t nb1, nb2;
-    stats_grid(n, nb1, nb2);
+    stats_grid(n, dtype, nb1, nb2);
     hipLaunchKernelGGL(k_stats_finalize, dim3(1), dim3(kFinThreads), 0, s, reinterpret_cast<const Part1 *>(w + kOffPart1),
                        nb1, reinterpret_cast<const Part2 *>(w + kOffPart2), nb2,
                        reinterpret_cast<const uint32_t *>(w + kOffHist), nbins, n,
@@ -246,17 +271,23 @@ hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, vo
     uint32_t *hist = reinterpret_cast<uint32_t *>(w + kOffHist);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
     uint32_t nb1, nb2;
-    stats_grid(n, nb1, nb2);
-    if (dtype == QP_F32) {
+    stats_grid(n, dtype, nb1, nb2);
+    if (dtype == QP_F32)
         hipLaunchKernelGGL(k_stats_pass1<QP_F32>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
-        hipLaunchKernelGGL(k_stats_pass2<QP_F32>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins);
-    } else {
+    else
         hipLaunchKernelGGL(k_stats_pass1<QP_BF16>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
-        hipLaunchKernelGGL(k_stats_pass2<QP_BF16>, dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins);
+#define QP_PASS2(DT, R) \
+    hipLaunchKernelGGL((k_stats_pass2<DT, R>), dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins)
+    const uint32_t rs = hist_rep_shift(nbins);
+    if (dtype == QP_F32) {
+        if (rs == 3) QP_PASS2(QP_F32, 3); else if (rs == 2) QP_PASS2(QP_F32, 2); else QP_PASS2(QP_F32, 1);
+    } else {
+        if (rs == 3) QP_PASS2(QP_BF16, 3); else if (rs == 2) QP_PASS2(QP_BF16, 2); else QP_PASS2(QP_BF16, 1);
     }
+#undef QP_PASS2
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !finalize) return e;
-    return launch_stats_finalize(n, nbins, ws, s);
+    return launch_stats_finalize(n, dtype, nbins, ws, s);
 }
 
 }  // namespace qp
