@@ -570,3 +570,93 @@ def test_largest_supported_tensor(qp):
         # the score of the winner on a periodic tensor: reps * block + remainder, from the oracle
         e_block = pairwise_sq_error(orc.widen_bf16(block), oq)
         del packed, y
+
+
+# ----------------------------------------------------------------------------- sender path on edge cases, graphs, streams
+
+@pytest.mark.parametrize("name,x", si.edge_cases(), ids=[c[0] for c in si.edge_cases()])
+def test_fused_sender_path_on_edge_cases(qp, name, x):
+    """qp_compress_async (statistics finalized inside the search set-up) equals the step-by-step path."""
+    xd = to_dev(x)
+    n = x.size
+    for bits in (2, 6):
+        ws = qp.alloc_workspace(n)
+        st = qp.qp_stats(xd, ws)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        p_ref = qp.alloc_packed(n, bits)
+        qp.qp_quant_pack(xd, q, p_ref)
+        ws2 = qp.alloc_workspace(n)
+        ws2.fill_(0xC3)
+        p_dev = qp.alloc_packed(n, bits)
+        qp.qp_compress_async(xd, bits, ws2, p_dev)
+        torch.cuda.synchronize()
+        assert bytes(qp.read_ws(ws2, qp.QP_WS_STATS, qp.qp_stats_t)) == bytes(st)
+        assert bytes(qp.read_ws(ws2, qp.QP_WS_QPARAMS, qp.qp_qparams_t)) == bytes(q)
+        r2 = qp.read_ws(ws2, qp.QP_WS_RESULT, qp.qp_search_result_t)
+        assert bytes(r2) == bytes(res) or (np.isnan(res.mse_star) and r2.j_star == res.j_star)
+        assert torch.equal(p_ref, p_dev)
+
+
+def test_sender_and_receiver_replay_from_a_hip_graph(qp):
+    """The async entry points launch kernels only (no allocation, no memset, no host sync), so they
+    capture into a HIP graph; every replay must reproduce the eager result."""
+    x1 = si.make_config("C2", n=700_003)
+    x2 = si.make_config("C3", n=700_003)
+    n = x1.size
+    xin = to_dev(x1).clone()
+    ws = qp.alloc_workspace(n)
+    packed = qp.alloc_packed(n, 4)
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    qdev = ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS)
+
+    def run():
+        qp.qp_compress_async(xin, 4, ws, packed)
+        qp.qp_unpack_dequant_dev(packed, 4, qdev, y)
+
+    def eager(src):
+        xin.copy_(to_dev(src))
+        run()
+        torch.cuda.synchronize()
+        return packed.clone(), y.clone(), bytes(qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t))
+
+    ref1, ref2 = eager(x1), eager(x2)
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        run()                                   # warm the stream (and the library's occupancy cache)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        run()
+    torch.cuda.synchronize()
+    for rep, (src, ref) in enumerate(((x1, ref1), (x2, ref2), (x1, ref1), (x2, ref2))):
+        xin.copy_(to_dev(src))
+        packed.zero_()
+        y.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(packed, ref[0]) and torch.equal(y, ref[1]), rep
+        assert bytes(qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)) == ref[2], rep
+
+
+def test_two_streams_with_their_own_workspaces(qp):
+    xa, xb = si.make_config("C2", n=900_001), si.make_config("C3", n=1_100_003)
+    da, db = to_dev(xa), to_dev(xb)
+    wa, wb = qp.alloc_workspace(xa.size), qp.alloc_workspace(xb.size)
+    pa, pb = qp.alloc_packed(xa.size, 3), qp.alloc_packed(xb.size, 8)
+    ra_, rb_ = qp.alloc_packed(xa.size, 3), qp.alloc_packed(xb.size, 8)
+    qp.qp_compress_async(da, 3, wa, ra_)
+    qp.qp_compress_async(db, 8, wb, rb_)
+    torch.cuda.synchronize()
+    ref = (bytes(qp.read_ws(wa, qp.QP_WS_RESULT, qp.qp_search_result_t)), bytes(qp.read_ws(wb, qp.QP_WS_RESULT, qp.qp_search_result_t)))
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(5):
+        pa.zero_(); pb.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sa):
+            qp.qp_compress_async(da, 3, wa, pa)
+        with torch.cuda.stream(sb):
+            qp.qp_compress_async(db, 8, wb, pb)
+        torch.cuda.synchronize()
+        assert torch.equal(pa, ra_) and torch.equal(pb, rb_)
+        assert (bytes(qp.read_ws(wa, qp.QP_WS_RESULT, qp.qp_search_result_t)), bytes(qp.read_ws(wb, qp.QP_WS_RESULT, qp.qp_search_result_t))) == ref
