@@ -373,3 +373,52 @@ int orc_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_rate,
     *q_next = 32u >> (uint32_t)e;
     return 0;
 }
+
+/* ---- DS-ACIQ, the other reading of Eq. 1: fit the Laplace pdf to the histogram -------
+ *
+ * Eq. 1 literally minimises MSE(D_R, D_E) between the real distribution D_R (the histogram,
+ * as a density) and the estimated one D_E (the Laplace pdf with scale b) over b in
+ * [b_E, b_R].  Same candidate grid and first-minimum rule as the tensor-error search;
+ * the score of candidate j is the sum over bins of (D_R,i - pdf(c_i; mu, b_j))^2 with
+ * c_i the bin centre, D_R,i = count_i / (N binwidth), pdf = exp(-|c - mu| / b) / (2 b).
+ * mse_* are the means over the bins.  No pass over the tensor.
+ */
+int orc_hist_search(const orc_stats_t *st, const uint32_t *hist, uint32_t bits, uint32_t t_steps,
+                    orc_search_result_t *res, orc_qparams_t *best_q, double *scores)
+{
+    if (!orc_bits_ok(bits) || t_steps == 0 || st->n == 0 || st->nbins == 0) return 2;
+    const uint32_t B = st->nbins;
+    double F = orc_laplace_F(bits);
+    double b_e = st->mad, b_r = st->b_r;
+    double step = (b_r - b_e) / (double)t_steps;
+    if (!(b_e > 0.0) || !(b_r > 0.0) || !isfinite(b_r) || !isfinite(b_e) || !isfinite(step))
+        step = 0.0;
+    double binw = (st->max - st->min) / (double)B;
+    uint32_t best_j = 0;
+    double best = 0.0, first = 0.0;
+    for (uint32_t j = 0; j <= t_steps; ++j) {
+        double b_j = b_e + (double)j * step;
+        double s = 0.0;
+        for (uint32_t i = 0; i < B; ++i) {
+            double c = st->min + ((double)i + 0.5) * binw;
+            double d_r = (double)hist[i] / ((double)st->n * binw);
+            double d_e = exp(-fabs(c - st->mean) / b_j) / (2.0 * b_j);
+            double diff = d_r - d_e;
+            s += diff * diff;
+        }
+        if (scores) scores[j] = s;
+        if (j == 0) first = s;
+        if (j == 0 || s < best) { best = s; best_j = j; }
+    }
+    double b_star = b_e + (double)best_j * step;
+    res->b_e = b_e;
+    res->b_r = b_r;
+    res->b_star = b_star;
+    res->alpha_star = F * b_star;
+    res->j_star = best_j;
+    res->t_steps = t_steps;
+    res->mse_aciq = first / (double)B;
+    res->mse_star = best / (double)B;
+    if (best_q) orc_make_qparams(st->mean, res->alpha_star, bits, st->n, best_q);
+    return 0;
+}

@@ -84,6 +84,9 @@ def lib():
         L.orc_dsaciq_search.argtypes = [fp, C.c_uint64, C.POINTER(Stats), C.c_uint32, C.c_uint32,
                                         C.POINTER(SearchResult), C.POINTER(QParams), dp]
         L.orc_dsaciq_search.restype = C.c_int
+        L.orc_hist_search.argtypes = [C.POINTER(Stats), u32p, C.c_uint32, C.c_uint32, C.POINTER(SearchResult),
+                                      C.POINTER(QParams), dp]
+        L.orc_hist_search.restype = C.c_int
         L.orc_next_bits.argtypes = [C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_uint32)]
         L.orc_next_bits.restype = C.c_int
         _lib = L
@@ -215,3 +218,17 @@ def next_bits(v_bits, q_cur, s_images, r_rate, bandwidth):
     if rc:
         raise ValueError("orc_next_bits: bad argument")
     return out.value
+
+
+def hist_search(st, hist, bits, t_steps=100):
+    """Histogram-fit reading of Eq. 1.  Returns (SearchResult, QParams of the winner, scores[t+1])."""
+    h, p = _u32(hist)
+    if h.size < st.nbins:
+        raise ValueError("histogram shorter than st.nbins")
+    res, q = SearchResult(), QParams()
+    scores = np.zeros(t_steps + 1, dtype=np.float64)
+    rc = lib().orc_hist_search(C.byref(st), p, int(bits), int(t_steps), C.byref(res), C.byref(q),
+                               scores.ctypes.data_as(C.POINTER(C.c_double)))
+    if rc:
+        raise ValueError("orc_hist_search: bad argument")
+    return res, q, scores

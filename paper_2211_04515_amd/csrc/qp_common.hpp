@@ -13,8 +13,8 @@ constexpr int kWave = 64;
 constexpr uint32_t kMaxBins = 4096;
 constexpr uint32_t kMaxT = 1023;           // candidates j = 0..t, t <= kMaxT
 constexpr uint32_t kMaxCandsPerRound = 32;
-constexpr uint32_t kMaxStat1Blocks = 1024; // capacity of the pass-1 partial array
-constexpr uint32_t kMaxStat2Blocks = 512;
+constexpr uint32_t kMaxStat1Blocks = 512;  // most blocks of statistics pass 1 (256 lanes each)
+constexpr uint32_t kMaxStat2Blocks = 256;  // most blocks of pass 2 (512 lanes each): one per CU measured best
 constexpr uint32_t kMaxSearchBlocks = 1024;
 
 // Per-block partial of the first statistics pass.

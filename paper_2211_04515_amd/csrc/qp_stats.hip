@@ -8,7 +8,7 @@
 // Accumulation is fp64 per lane, reduced inside each wave64 with DPP lane permutations, one
 // LDS slot per wave, then across blocks in a fixed order: no floating-point atomics, so
 // results are bit-reproducible from run to run.  Pass 2 needs mu, min and max; every block of
-// pass 2 re-reduces the (at most 1024) pass-1 partials itself, with its first loads of the
+// pass 2 re-reduces the (at most 512) pass-1 partials itself, with its first loads of the
 // tensor already in flight, which saves a launch and a grid-wide dependency.  A one-block
 // kernel after pass 2 (or the search's set-up kernel, when the search follows) turns the
 // partials and the histogram into the qp_stats_t record: kernel boundaries order the memory,

@@ -468,3 +468,64 @@ def test_eq2_picks_the_highest_power_of_two_that_fits():
         budget = s_img / rate * bw
         fitting = [k for k in (32, 16, 8, 4, 2) if n * k <= budget]
         assert q == (max(fitting) if fitting else 2)
+
+
+# ----------------------------------------------------------------------------- histogram-fit reading of Eq. 1
+
+def _laplace_cdf(x, mu, b):
+    z = (x - mu) / b
+    return np.where(z < 0, 0.5 * np.exp(z), 1.0 - 0.5 * np.exp(-z))
+
+
+def _exact_laplace_histogram(mu, b, lo, hi, nbins, n):
+    edges = np.linspace(lo, hi, nbins + 1)
+    mass = np.diff(_laplace_cdf(edges, mu, b))
+    return np.round(mass / mass.sum() * n).astype(np.uint32)
+
+
+def test_hist_search_recovers_the_scale_of_an_exact_laplace_histogram():
+    # counts taken from the Laplace cdf itself: the pdf that fits them best has the true scale,
+    # wherever the interval [b_E, b_R] starts and ends, and in both directions
+    mu, b, n, nbins = 0.3, 0.7, 50_000_000, 2048
+    for lo_b, hi_b in ((0.35, 1.4), (1.4, 0.35), (0.6, 0.8)):
+        st = orc.Stats()
+        st.n, st.nbins, st.mean, st.min, st.max = n, nbins, mu, mu - 12 * b, mu + 12 * b
+        st.mad, st.b_r = lo_b, hi_b
+        hist = _exact_laplace_histogram(mu, b, st.min, st.max, nbins, n)
+        st.n = int(hist.sum())
+        res, q, scores = orc.hist_search(st, hist, 4, 100)
+        grid_step = abs(hi_b - lo_b) / 100
+        assert abs(res.b_star - b) <= grid_step, (lo_b, hi_b, res.b_star)
+        assert res.mse_star <= res.mse_aciq and res.j_star == int(np.argmin(scores))
+        assert res.alpha_star == pytest.approx(orc.laplace_F(4) * res.b_star, rel=1e-15)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_hist_search_matches_independent_numpy_statement(name):
+    x = si.make_config(name, n=300_000)
+    rc, st, hist = orc.stats(x, want_hist=True)
+    res, q, scores = orc.hist_search(st, hist, 2, 100)
+    binw = (st.max - st.min) / st.nbins
+    c = st.min + (np.arange(st.nbins) + 0.5) * binw
+    d_r = hist[:st.nbins].astype(np.float64) / (st.n * binw)
+    ref = []
+    for j in range(101):
+        bj = st.mad + j * ((st.b_r - st.mad) / 100)
+        d_e = np.exp(-np.abs(c - st.mean) / bj) / (2 * bj)
+        ref.append(float(np.sum((d_r - d_e) ** 2)))
+    ref = np.array(ref)
+    assert np.allclose(scores, ref, rtol=1e-12, atol=0)
+    assert res.j_star == int(np.argmin(ref)) or abs(ref[res.j_star] - ref.min()) <= 1e-12 * ref.min()
+    assert res.mse_aciq == pytest.approx(ref[0] / st.nbins, rel=1e-12)
+    lo_b, hi_b = sorted((st.mad, st.b_r))
+    assert lo_b <= res.b_star <= hi_b
+    oq = orc.make_qparams(st.mean, res.alpha_star, 2, x.size)
+    assert (q.lo, q.hi, q.scale) == (oq.lo, oq.hi, oq.scale)
+
+
+def test_hist_search_degenerate_keeps_b_e():
+    x = np.full(100, 3.0, np.float32)
+    rc, st, hist = orc.stats(x, want_hist=True)
+    st.mad = 0.5          # pretend a scale; the bound is 0, so the grid collapses
+    res, q, scores = orc.hist_search(st, hist, 4, 50)
+    assert res.j_star == 0 and res.b_star == 0.5
