@@ -172,6 +172,8 @@ def main() -> int:
         byts = in_bytes + n * b / 8
         per_bits[str(b)] = {"pack_us": tp, "pack_GBs": byts / tp / 1e3, "unpack_us": tu, "unpack_GBs": byts / tu / 1e3}
     ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % NBUF], ws))
+    # the histogram-fit reading of Eq. 1 works on the 2048-bin histogram only (no tensor pass)
+    th = timed_reps(lambda r: qp.qp_dsaciq_hist_search_async(4, ws))
 
     def hbm(kernel, byts, us, key):
         a = byts / us / 1e3
@@ -210,6 +212,7 @@ def main() -> int:
         "ms_per_step_instrumented": ms_per_step_instrumented,
         "stage_us": {k: mean(v) for k, v in stage.items()},
         "dsaciq_us_per_tensor": search_us,
+        "dsaciq_histogram_fit_us_per_tensor": th,
         "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
         "per_bitwidth": per_bits,
         "large_tensor_bf16": large,

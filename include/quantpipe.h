@@ -171,6 +171,19 @@ qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const 
 qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
                                  const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* ---- step 2b, the other reading of Eq. 1: fit the estimated distribution to the histogram ----
+ * Eq. 1 as printed minimises MSE(D_R, D_E) between the real distribution D_R (the histogram of
+ * the tensor, as a density) and the estimated one D_E (the Laplace pdf with scale b) over
+ * b in [b_E, b_R].  Same candidate grid and first-minimum rule as qp_dsaciq_search; the score
+ * of candidate j is sum over bins of (D_R,i - exp(-|c_i - mu| / b_j) / (2 b_j))^2 with c_i the
+ * bin centre and D_R,i = count_i / (N binwidth); mse_aciq / mse_star are means over the bins.
+ * Works on the statistics record and histogram that qp_stats / qp_stats_async left in ws_dev
+ * (no pass over the tensor) and overwrites QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES. */
+qp_status qp_dsaciq_hist_search(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
+                                void *stream, qp_search_result_t *res_host, qp_qparams_t *qparams_out_host);
+qp_status qp_dsaciq_hist_search_async(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
+                                      void *stream);
+
 /* ---- step 3: clip + uniform quantize + bit-pack (Sec. 3: ACIQ clipping, then PTQ) ----
  * c_i = rne((min(max(x_i, lo), hi) - lo) * inv_scale) clamped to [0, 2^bits - 1]
  * (fp32: one subtraction, one product, round half to even; NaN -> code 0), written in

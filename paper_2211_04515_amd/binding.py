@@ -17,7 +17,7 @@ __all__ = [
     "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "QuantPipeError", "BITS",
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
     "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_dsaciq_search",
-    "qp_dsaciq_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
+    "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
     "qp_compress_async", "qp_next_bits", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
 ]
 
@@ -84,6 +84,9 @@ def lib():
             "qp_dsaciq_search": (i32, [vp, u64, i32, C.POINTER(qp_stats_t), u32, C.POINTER(qp_search_cfg_t), vp, sz,
                                        vp, C.POINTER(qp_search_result_t), C.POINTER(qp_qparams_t)]),
             "qp_dsaciq_search_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp]),
+            "qp_dsaciq_hist_search": (i32, [u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, C.POINTER(qp_search_result_t),
+                                            C.POINTER(qp_qparams_t)]),
+            "qp_dsaciq_hist_search_async": (i32, [u32, C.POINTER(qp_search_cfg_t), vp, sz, vp]),
             "qp_quant_pack": (i32, [vp, u64, i32, C.POINTER(qp_qparams_t), vp, sz, vp]),
             "qp_quant_pack_dev": (i32, [vp, u64, i32, u32, vp, vp, sz, vp]),
             "qp_unpack_dequant": (i32, [vp, sz, C.POINTER(qp_qparams_t), vp, u64, vp]),
@@ -102,7 +105,7 @@ def lib():
 
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
            "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_dsaciq_search",
-           "qp_dsaciq_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
+           "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
            "qp_unpack_dequant_dev", "qp_compress_async", "qp_next_bits", "qp_strerror")
 
 
@@ -262,3 +265,16 @@ def qp_next_bits(v_bits: float, q_cur: int, s_images: float, r_images_per_s: flo
     _check(lib().qp_next_bits(float(v_bits), int(q_cur), float(s_images), float(r_images_per_s),
                               float(bandwidth_bits_per_s), C.byref(out)), "qp_next_bits")
     return out.value
+
+
+def qp_dsaciq_hist_search(bits: int, ws, cfg=None, stream=None):
+    """Histogram-fit reading of Eq. 1 on the statistics left in ws.  Returns (result, qparams)."""
+    res, q = qp_search_result_t(), qp_qparams_t()
+    _check(lib().qp_dsaciq_hist_search(int(bits), _cfgp(cfg), _dev(ws), ws.numel(), _stream(stream), C.byref(res),
+                                       C.byref(q)), "qp_dsaciq_hist_search")
+    return res, q
+
+
+def qp_dsaciq_hist_search_async(bits: int, ws, cfg=None, stream=None) -> None:
+    _check(lib().qp_dsaciq_hist_search_async(int(bits), _cfgp(cfg), _dev(ws), ws.numel(), _stream(stream)),
+           "qp_dsaciq_hist_search_async")

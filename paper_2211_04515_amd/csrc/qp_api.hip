@@ -201,6 +201,33 @@ qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const 
     return QP_OK;
 }
 
+qp_status qp_dsaciq_hist_search_async(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
+                                      void *stream)
+{
+    if (!bits_ok(bits) || check_cfg(cfg) != QP_OK) return QP_EINVAL;
+    if (!ws_dev || !aligned16(ws_dev)) return QP_EINVAL;
+    if (ws_bytes < kOffSearchPart) return QP_ENOSPC;   // only the fixed-size head of the workspace is used
+    const uint32_t t = cfg ? cfg->t_steps : 100u;
+    return hip_status(launch_hist_search(bits, t, laplace_constant(bits), ws_dev, static_cast<hipStream_t>(stream)));
+}
+
+qp_status qp_dsaciq_hist_search(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream,
+                                qp_search_result_t *res_host, qp_qparams_t *qparams_out_host)
+{
+    const qp_status st = qp_dsaciq_hist_search_async(bits, cfg, ws_dev, ws_bytes, stream);
+    if (st != QP_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws_dev);
+    if (res_host &&
+        hipMemcpyAsync(res_host, w + kOffResult, sizeof(qp_search_result_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return QP_EHIP;
+    if (qparams_out_host &&
+        hipMemcpyAsync(qparams_out_host, w + kOffQParams, sizeof(qp_qparams_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return QP_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return QP_EHIP;
+    return QP_OK;
+}
+
 static qp_status pack_common(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_qparams_t *hq,
                              const qp_qparams_t *dq, void *packed_dev, size_t packed_bytes, void *stream)
 {

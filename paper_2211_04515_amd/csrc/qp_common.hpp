@@ -401,6 +401,7 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
                          hipStream_t s);
 hipError_t launch_stats_finalize(uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s);
 uint32_t search_blocks(uint64_t n);
+hipError_t launch_hist_search(uint32_t bits, uint32_t t_steps, double F, void *ws, hipStream_t s);
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *host_qp,
                              const qp_qparams_t *dev_qp, void *packed, hipStream_t s);
 hipError_t launch_unpack_dequant(const void *packed, uint32_t bits, const qp_qparams_t *host_qp,

@@ -273,6 +273,106 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     }
 }
 
+// ---- the other reading of Eq. 1: fit the Laplace pdf to the histogram -----------------
+// One block per candidate: lanes stride over the bins, score_j = sum_i (D_R,i - pdf(c_i; mu, b_j))^2
+// in fp64 (D_R,i = count_i / (N binwidth), c_i the bin centre).  The block that draws the last
+// ticket takes the first minimum, as in the tensor-error search.  Reads the statistics record
+// and the histogram that the statistics step left in the workspace; no pass over the tensor.
+constexpr int kHsThreads = 256;
+__global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__restrict__ st,
+                                                            const uint32_t *__restrict__ hist, uint32_t bits,
+                                                            uint32_t t_steps, double F, double *__restrict__ scores,
+                                                            Ctl *__restrict__ ctl, qp_search_result_t *__restrict__ res,
+                                                            qp_qparams_t *__restrict__ best)
+{
+    __shared__ double sh[kHsThreads / kWave];
+    __shared__ uint32_t sh_flag;
+    const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const uint32_t j = blockIdx.x, ncand = t_steps + 1u;
+    const uint32_t B = st->nbins;
+    const uint64_t n = st->n;
+    const double mean = st->mean, mn = st->min, mx = st->max;
+    const double b_e = st->mad, b_r = st->b_r;
+    double step = (b_r - b_e) / (double)t_steps;
+    const bool ok = (b_e > 0.0) && (b_r > 0.0) && isfinite(b_r) && isfinite(b_e) && isfinite(step);
+    if (!ok) step = 0.0;
+    const double b_j = b_e + (double)j * step;
+    const double binw = (mx - mn) / (double)B;
+    double s = 0.0;
+    for (uint32_t i = tid; i < B; i += kHsThreads) {
+        const double c = mn + ((double)i + 0.5) * binw;
+        const double d_r = (double)hist[i] / ((double)n * binw);
+        const double d_e = exp(-fabs(c - mean) / b_j) / (2.0 * b_j);
+        const double diff = d_r - d_e;
+        s = fma(diff, diff, s);
+    }
+    s = wave_sum(s);
+    if (lane == 0) sh[wave] = s;
+    __syncthreads();
+    if (tid == 0) {
+        double tot = sh[0];
+        for (int w = 1; w < kHsThreads / kWave; ++w) tot += sh[w];
+        scores[j] = tot;
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, QP_TICKET_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+        sh_flag = (prev == gridDim.x - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!sh_flag || wave != 0) return;
+    QP_TICKET_ACQUIRE();
+
+    double bs = INFINITY;
+    uint32_t bj = 0xffffffffu;
+    for (uint32_t k = lane; k < ncand; k += kWave) {
+        const double v = scores[k];
+        if (bj == 0xffffffffu || v < bs) {
+            bs = (v == v) ? v : INFINITY;
+            bj = k;
+        }
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const double os = __shfl_xor(bs, o, kWave);
+        const uint32_t oj = __shfl_xor(bj, o, kWave);
+        if (os < bs || (os == bs && oj < bj)) {
+            bs = os;
+            bj = oj;
+        }
+    }
+    if (lane == 0) {
+        const double s0 = scores[0];
+        if (!(s0 == s0)) bj = 0u;
+        qp_search_result_t r;
+        r.b_e = b_e;
+        r.b_r = b_r;
+        r.b_star = b_e + (double)bj * step;
+        r.alpha_star = F * r.b_star;
+        r.mse_aciq = s0 / (double)B;
+        r.mse_star = scores[bj] / (double)B;
+        r.j_star = bj;
+        r.t_steps = t_steps;
+        *res = r;
+        qp_qparams_t q;
+        q.bits = bits;
+        q.reserved = 0u;
+        q.n = n;
+        make_grid(mean, r.alpha_star, bits, q.lo, q.hi, q.scale, q.inv_scale);
+        *best = q;
+        ctl->ticket_search = 0u;
+    }
+}
+
+hipError_t launch_hist_search(uint32_t bits, uint32_t t_steps, double F, void *ws, hipStream_t s)
+{
+    char *w = static_cast<char *>(ws);
+    hipLaunchKernelGGL(k_hist_search, dim3(t_steps + 1u), dim3(kHsThreads), 0, s,
+                       reinterpret_cast<const qp_stats_t *>(w + kOffStats),
+                       reinterpret_cast<const uint32_t *>(w + kOffHist), bits, t_steps, F,
+                       reinterpret_cast<double *>(w + kOffScores), reinterpret_cast<Ctl *>(w + kOffCtl),
+                       reinterpret_cast<qp_search_result_t *>(w + kOffResult),
+                       reinterpret_cast<qp_qparams_t *>(w + kOffQParams));
+    return hipGetLastError();
+}
+
 // Upper bound on the number of block columns (sizes the partial-sum region of the workspace).
 uint32_t search_blocks(uint64_t n)
 {

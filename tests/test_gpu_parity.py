@@ -660,3 +660,55 @@ def test_two_streams_with_their_own_workspaces(qp):
         torch.cuda.synchronize()
         assert torch.equal(pa, ra_) and torch.equal(pb, rb_)
         assert (bytes(qp.read_ws(wa, qp.QP_WS_RESULT, qp.qp_search_result_t)), bytes(qp.read_ws(wb, qp.QP_WS_RESULT, qp.qp_search_result_t))) == ref
+
+
+# ----------------------------------------------------------------------------- histogram-fit reading of Eq. 1
+
+HIST_CASES = [("C1", None), ("C2", 1_234_567), ("C3", 987_653), ("C5", 777_779)]
+
+
+@pytest.mark.parametrize("name,n", HIST_CASES, ids=[c[0] for c in HIST_CASES])
+def test_hist_search_matches_oracle(qp, name, n):
+    x = si.make_config(name, n=n)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    hist = ws[off:off + 4 * 2048].cpu().numpy().view(np.uint32).copy()
+    offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for bits, t in ((2, 100), (4, 100), (8, 37)):
+        cfg = qp.qp_default_search_cfg()
+        cfg.t_steps = t
+        res, q = qp.qp_dsaciq_hist_search(bits, ws, cfg=cfg)
+        scores = ws[offs:offs + 8 * (t + 1)].cpu().numpy().view(np.float64)
+        ores, oq, oscores = orc.hist_search(oracle_stats_from(st), hist, bits, t)
+        # the device's exp and libm's may differ in the last place; sums of 2048 terms
+        assert np.allclose(scores, oscores, rtol=1e-12, atol=0.0)
+        if res.j_star == ores.j_star:
+            assert res.alpha_star == pytest.approx(ores.alpha_star, rel=1e-14)
+            assert (q.lo, q.hi, q.scale, q.inv_scale, q.bits, q.n) == (oq.lo, oq.hi, oq.scale, oq.inv_scale, bits, x.size)
+        else:
+            assert abs(oscores[res.j_star] - oscores[ores.j_star]) <= 1e-12 * oscores[ores.j_star]
+        assert res.mse_star == pytest.approx(ores.mse_star, rel=1e-12) and res.mse_star <= res.mse_aciq
+        assert res.t_steps == t
+    # the winner's grid is usable as it is: pack with it straight from the workspace
+    packed = qp.alloc_packed(x.size, 8)
+    qp.qp_quant_pack_dev(xd, 8, ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), packed)
+    assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(as_f32(x), oracle_q_from(q)), 8))
+
+
+@pytest.mark.parametrize("name", ["constant", "zeros", "two_point", "laplace_n1", "huge_outlier", "large_values"])
+def test_hist_search_degenerate_inputs(qp, name):
+    x = dict(si.edge_cases())[name]
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    hist = ws[off:off + 4 * 2048].cpu().numpy().view(np.uint32).copy()
+    res, q = qp.qp_dsaciq_hist_search(4, ws)
+    ores, oq, oscores = orc.hist_search(oracle_stats_from(st), hist, 4, 100)
+    offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    scores = ws[offs:offs + 8 * 101].cpu().numpy().view(np.float64)
+    assert np.allclose(scores, oscores, rtol=1e-12, atol=0.0, equal_nan=True)
+    assert res.j_star == ores.j_star
+    assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)

@@ -139,6 +139,12 @@ def test_argument_errors_are_reported_before_any_gpu_work(qp):
     cfg = qp.qp_default_search_cfg()
     cfg.t_steps = 5000
     assert L.qp_dsaciq_search_async(fake, 1000, 0, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
+    # histogram-fit search
+    assert L.qp_dsaciq_hist_search_async(5, None, fake, big, None) == qp.QP_EINVAL
+    assert L.qp_dsaciq_hist_search_async(4, None, None, big, None) == qp.QP_EINVAL
+    assert L.qp_dsaciq_hist_search_async(4, None, odd, big, None) == qp.QP_EINVAL
+    assert L.qp_dsaciq_hist_search_async(4, None, fake, 1000, None) == qp.QP_ENOSPC
+    assert L.qp_dsaciq_hist_search(4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL   # t_steps 5000
     # pack
     assert L.qp_quant_pack(fake, 1000, 0, None, fake, big, None) == qp.QP_EINVAL
     assert L.qp_quant_pack(fake, 999, 0, C.byref(q), fake, big, None) == qp.QP_EINVAL        # n mismatch
