@@ -19,6 +19,8 @@
 //     No floating-point atomics: bit-reproducible.
 // The per-element arithmetic is that of quantize+pack and unpack+dequantize, so a candidate's
 // score is exactly the error of the tensor that would come out of the receiver.
+#include <atomic>
+
 #include "qp_common.hpp"
 
 namespace qp {
@@ -387,18 +389,20 @@ uint32_t search_blocks(uint64_t n)
 // own occupancy); the grid is sized to this so that there is one wave of blocks and no tail.
 template <int DT, int CMAX> static uint32_t resident_blocks()
 {
-    static uint32_t cached[16] = {0};
+    static std::atomic<uint32_t> cached[16];   // zero-initialised; a race only repeats the same query
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-    if (cached[dev] == 0) {
+    uint32_t v = cached[dev].load(std::memory_order_relaxed);
+    if (v == 0) {
         int per_cu = 0, cus = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_search_mse<DT, CMAX>, kSrThreads, 0) != hipSuccess ||
             per_cu < 1)
             per_cu = 2;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-        cached[dev] = (uint32_t)per_cu * (uint32_t)cus;
+        v = (uint32_t)per_cu * (uint32_t)cus;
+        cached[dev].store(v, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return v;
 }
 
 struct SearchArgs {
