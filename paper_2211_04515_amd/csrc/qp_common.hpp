@@ -63,7 +63,8 @@ constexpr size_t kOffScores = kOffCands + (kMaxT + 1) * sizeof(Cand);   // doubl
 constexpr size_t kOffRoundTickets = kOffScores + (kMaxT + 1) * 8; // uint32_t[kMaxT + 1]: per-round block counters
 constexpr size_t kOffPart1 = kOffRoundTickets + (kMaxT + 1) * 4;  // Part1[kMaxStat1Blocks]
 constexpr size_t kOffPart2 = kOffPart1 + kMaxStat1Blocks * sizeof(Part1);  // Part2[kMaxStat2Blocks]
-constexpr size_t kOffSearchPart = kOffPart2 + kMaxStat2Blocks * sizeof(Part2);  // double[t + 1][blocks]
+constexpr size_t kOffValueCounts = kOffPart2 + kMaxStat2Blocks * sizeof(Part2);  // uint32_t[65536]: bf16 value table
+constexpr size_t kOffSearchPart = kOffValueCounts + 65536 * 4;  // double[t + 1][blocks]
 static_assert(sizeof(qp_stats_t) <= 128 && sizeof(qp_search_result_t) <= 64 && sizeof(qp_qparams_t) == 32 &&
               sizeof(Ctl) <= 256, "fixed workspace regions");
 static_assert(kOffSearchPart % 16 == 0, "alignment");

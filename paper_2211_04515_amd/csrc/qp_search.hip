@@ -25,6 +25,13 @@
 
 namespace qp {
 
+// Internal pseudo element type: the "tensor" is the table of all 65536 bfloat16 bit patterns and
+// x points at their counts (see k_value_hist_bf16); element i has the value of pattern i and the
+// weight counts[i].
+constexpr int kValues16 = 2;
+constexpr uint32_t kNumValues16 = 65536;
+// bf16 tensors at least this large are searched through their value table
+constexpr uint64_t kValueTableMinN = 1ull << 19;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
@@ -51,9 +58,12 @@ __global__ __launch_bounds__(kFinThreads) void k_search_setup(qp_stats_t *__rest
                                                               double b_e_h, double b_r_h, int from_ws, uint32_t bits,
                                                               uint32_t t_steps, double F, uint64_t n,
                                                               Cand *__restrict__ cands, Ctl *__restrict__ ctl,
-                                                              uint32_t *__restrict__ round_tickets, FinalizeArgs fin)
+                                                              uint32_t *__restrict__ round_tickets, FinalizeArgs fin,
+                                                              uint32_t *__restrict__ value_counts)
 {
     for (uint32_t j = threadIdx.x; j <= kMaxT; j += blockDim.x) round_tickets[j] = 0u;
+    if (value_counts)   // the bf16 value table is accumulated with atomics by the next kernel
+        for (uint32_t j = threadIdx.x; j < kNumValues16; j += blockDim.x) value_counts[j] = 0u;
     if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
     double mean = mean_h, b_e = b_e_h, b_r = b_r_h;
     if (from_ws) {
@@ -97,8 +107,9 @@ template <int DT, int CMAX, bool SHORT>
 __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t n, const Cand *sh_cands, uint32_t nc,
                                            float Lf, double (&acc)[CMAX])
 {
+    constexpr bool WEIGHTED = (DT == kValues16);
     const uint32_t tid = threadIdx.x;
-    auto score = [&](const float (&v)[kSrElems], int ne) {
+    auto score = [&](const float (&v)[kSrElems], const double (&w)[kSrElems], int ne) {
 #pragma unroll
         for (int c = 0; c < CMAX; ++c) {
             if ((uint32_t)c < nc) {   // wave-uniform
@@ -119,8 +130,16 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
                             r = quant_level(v[e], p.lo, p.hi, p.inv_scale, Lf);
                         }
                         const float err = v[e] - dequant_level(r, p.scale, p.lo);
-                        const double de = (double)err;
-                        acc[c] = fma(de, de, acc[c]);   // de*de is exact in fp64
+                        if constexpr (WEIGHTED) {
+                            // count * err^2: count < 2^32 and err has 24 significant bits, so count*err
+                            // is exact in fp64 and the term is rounded once, like an unweighted one.
+                            // Patterns that do not occur (count 0; also NaN/Inf patterns) contribute nothing.
+                            const double de = (w[e] != 0.0) ? (double)err : 0.0;
+                            acc[c] = fma(w[e] * de, de, acc[c]);
+                        } else {
+                            const double de = (double)err;
+                            acc[c] = fma(de, de, acc[c]);   // de*de is exact in fp64
+                        }
                     }
                 }
             }
@@ -130,22 +149,101 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
     const uint64_t nbatch = n / kSrElems;
     for (uint64_t b = (uint64_t)blockIdx.x * kSrThreads + tid; b < nbatch; b += (uint64_t)gridDim.x * kSrThreads) {
         float v[kSrElems];
+        double w[kSrElems];
+        if constexpr (WEIGHTED) {
+            const uint32_t *cnt = reinterpret_cast<const uint32_t *>(x);
 #pragma unroll
-        for (int q = 0; q < kSrElems / 4; ++q) {
-            float f[4];
-            Vec4<DT>::load(x, (kSrElems / 4) * b + q, f);
+            for (int q = 0; q < kSrElems / 4; ++q) {
+                const uint4 c4 = reinterpret_cast<const uint4 *>(cnt)[(kSrElems / 4) * b + q];
+                const uint32_t cc[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[4 * q + e] = f[e];
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t pattern = (uint32_t)(kSrElems * b) + 4 * q + e;
+                    v[4 * q + e] = __uint_as_float(pattern << 16);
+                    w[4 * q + e] = (double)cc[e];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < kSrElems / 4; ++q) {
+                float f[4];
+                Vec4<DT>::load(x, (kSrElems / 4) * b + q, f);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[4 * q + e] = f[e];
+                    w[4 * q + e] = 1.0;
+                }
+            }
         }
-        score(v, kSrElems);
+        score(v, w, kSrElems);
     }
     // ragged tail: fewer than kSrElems elements, taken by one lane of block column 0
-    const uint32_t rem = (uint32_t)(n - nbatch * kSrElems);
-    if (rem && blockIdx.x == 0 && tid == 0) {
-        float v[kSrElems];
+    if constexpr (!WEIGHTED) {
+        const uint32_t rem = (uint32_t)(n - nbatch * kSrElems);
+        if (rem && blockIdx.x == 0 && tid == 0) {
+            float v[kSrElems];
+            double w[kSrElems];
 #pragma unroll
-        for (int e = 0; e < kSrElems; ++e) v[e] = ((uint32_t)e < rem) ? Vec4<DT>::load1(x, nbatch * kSrElems + e) : 0.0f;
-        score(v, (int)rem);
+            for (int e = 0; e < kSrElems; ++e) {
+                v[e] = ((uint32_t)e < rem) ? Vec4<DT>::load1(x, nbatch * kSrElems + e) : 0.0f;
+                w[e] = 1.0;
+            }
+            score(v, w, (int)rem);
+        }
+    }
+}
+
+// The value table of a bfloat16 tensor: counts[p] = number of elements with bit pattern p.  A
+// bf16 tensor has at most 65536 distinct values, and the error of an element under a candidate
+// depends on its value only, so the search can run over the table (65536 weighted "elements")
+// instead of the tensor: the same sum of squared errors, grouped by value.
+// A block counts one sign (32768 patterns, 128 KB of LDS, plain u32 counters) of one chunk of the
+// tensor; blocks b and b+8 sit on the same XCD (blocks are dealt round-robin to the 8 XCDs) and
+// take the two signs of the same chunk, so the second reader of a chunk hits in that XCD's L2.
+constexpr int kVhThreads = 1024;
+constexpr int kVhUnroll = 4;
+__global__ __launch_bounds__(kVhThreads) void k_value_hist_bf16(const uint16_t *__restrict__ x, uint64_t n,
+                                                                uint32_t *__restrict__ counts)
+{
+    __shared__ uint32_t sh[32768];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t sign = (blockIdx.x >> 3) & 1u;
+    const uint32_t chunk = ((blockIdx.x >> 4) << 3) | (blockIdx.x & 7u);
+    const uint32_t nchunks = gridDim.x / 2;
+    for (uint32_t i = tid; i < 32768u; i += kVhThreads) sh[i] = 0u;
+    __syncthreads();
+    auto count = [&](uint32_t h) {
+        if ((h >> 15) == sign) atomicAdd(&sh[h & 0x7fffu], 1u);
+    };
+    const uint64_t nvec = n / 8;   // 16-byte vectors of 8 elements
+    const uint4 *__restrict__ x16 = reinterpret_cast<const uint4 *>(x);
+    const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;
+    uint64_t base = (uint64_t)chunk * tile;
+    const uint64_t stride = (uint64_t)nchunks * tile;
+    for (; base < nvec; base += stride) {
+        uint4 v[kVhUnroll];
+#pragma unroll
+        for (int u = 0; u < kVhUnroll; ++u) {
+            const uint64_t i = base + (uint64_t)u * kVhThreads + tid;
+            v[u] = (i < nvec) ? x16[i] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kVhUnroll; ++u) {
+            if (base + (uint64_t)u * kVhThreads + tid < nvec) {
+                const uint32_t wds[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    count(wds[k] & 0xffffu);
+                    count(wds[k] >> 16);
+                }
+            }
+        }
+    }
+    if (chunk == 0 && tid < (uint32_t)(n - nvec * 8)) count(x[nvec * 8 + tid]);
+    __syncthreads();
+    for (uint32_t i = tid; i < 32768u; i += kVhThreads) {
+        const uint32_t c = sh[i];
+        if (c) atomicAdd(&counts[(sign << 15) | i], c);
     }
 }
 
@@ -158,7 +256,7 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
                                                            double *__restrict__ scores, Ctl *__restrict__ ctl,
                                                            uint32_t *__restrict__ round_tickets,
                                                            qp_search_result_t *__restrict__ res,
-                                                           qp_qparams_t *__restrict__ best)
+                                                           qp_qparams_t *__restrict__ best, uint64_t n_total)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t c0 = blockIdx.y * cpr;
@@ -260,15 +358,15 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
         r.b_r = ctl->b_r;
         r.b_star = ctl->b_e + (double)bj * ctl->step;
         r.alpha_star = ctl->F * r.b_star;
-        r.mse_aciq = s0 / (double)n;
-        r.mse_star = sbest / (double)n;
+        r.mse_aciq = s0 / (double)n_total;
+        r.mse_star = sbest / (double)n_total;
         r.j_star = bj;
         r.t_steps = ncand - 1u;
         *res = r;
         qp_qparams_t q;
         q.bits = ctl->bits;
         q.reserved = 0u;
-        q.n = n;
+        q.n = n_total;
         make_grid(ctl->mean, r.alpha_star, ctl->bits, q.lo, q.hi, q.scale, q.inv_scale);
         *best = q;
         ctl->ticket_search = 0u;
@@ -416,6 +514,7 @@ struct SearchArgs {
     uint32_t *round_tickets;
     qp_search_result_t *res;
     qp_qparams_t *best;
+    uint64_t n_total;   // elements of the tensor (differs from n only on the value-table path)
 };
 
 // Picks the round structure and the grid for one kernel variant and launches it.
@@ -437,7 +536,7 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
     if (gx > cols) gx = cols;
     if (gx < 1) gx = 1;
     hipLaunchKernelGGL((k_search_mse<DT, CMAX>), dim3(gx, rounds), dim3(kSrThreads), 0, s, a.x, a.n, a.cands, a.ncand,
-                       cpr_eff, a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best);
+                       cpr_eff, a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.n_total);
     return hipGetLastError();
 }
 
@@ -453,16 +552,33 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
     FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                      reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
     if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
+    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
+    // them once (one pass over the tensor) and run the candidates over the value table.
+    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
+    uint32_t *value_counts = reinterpret_cast<uint32_t *>(w + kOffValueCounts);
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, stats_dev, st ? st->mean : 0.0,
                        st ? st->mad : 0.0, st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets,
-                       fin);
+                       fin, by_values ? value_counts : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
     SearchArgs a{x, n, cands, t_steps + 1u, cpr, (float)((1u << bits) - 1u),
                  reinterpret_cast<double *>(w + kOffSearchPart), reinterpret_cast<double *>(w + kOffScores), ctl,
                  round_tickets, reinterpret_cast<qp_search_result_t *>(w + kOffResult),
-                 reinterpret_cast<qp_qparams_t *>(w + kOffQParams)};
+                 reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n};
+    if (by_values) {
+        const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;               // 16-byte vectors per block step
+        uint64_t chunks = ((n / 8) + tile - 1) / tile;
+        chunks = (chunks + 7) / 8 * 8;                                        // whole groups of 8 (one per XCD)
+        if (chunks > 256) chunks = 256;
+        hipLaunchKernelGGL(k_value_hist_bf16, dim3((uint32_t)(2 * chunks)), dim3(kVhThreads), 0, s,
+                           static_cast<const uint16_t *>(x), n, value_counts);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.x = value_counts;
+        a.n = kNumValues16;
+        return cpr <= 16u ? launch_variant<kValues16, 16>(a, cpr, s) : launch_variant<kValues16, 32>(a, cpr, s);
+    }
     // the 16-candidate variant keeps three waves per SIMD resident, the 32-candidate one two (forcing more
     // waves only makes the compiler spill the accumulators)
     if (cpr <= 16u)
