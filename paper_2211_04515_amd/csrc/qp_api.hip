@@ -95,7 +95,10 @@ size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg)
     if (n == 0 || n > kMaxN) return 0;
     if (check_cfg(cfg) != QP_OK) return 0;
     const uint32_t t = cfg ? cfg->t_steps : 100u;
-    return kOffSearchPart + (size_t)search_blocks(n) * (t + 1u) * sizeof(double);
+    // partial sums: one column per block of whichever search kernel the size selects
+    uint32_t cols = search_blocks(n);
+    if (tile_search_eligible(n, t) && tile_search_blocks(n) > cols) cols = tile_search_blocks(n);
+    return kOffSearchPart + (size_t)cols * (t + 1u) * sizeof(double);
 }
 
 size_t qp_ws_offset(qp_ws_region region)
@@ -287,7 +290,7 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
     qp_status st = check_ws(n, cfg, ws_dev, ws_bytes);
     if (st != QP_OK) return st;
-    // the two statistics passes leave partials; the search's set-up kernel finalizes them
+    // the two statistics passes leave partials; the search finalizes them itself
     st = hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), false));
     if (st != QP_OK) return st;
     st = search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream, nbins);

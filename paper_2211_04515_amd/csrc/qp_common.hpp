@@ -43,7 +43,7 @@ static_assert(sizeof(Cand) == 16, "Cand layout");
 // Device-resident control block.
 struct Ctl {
     uint32_t reserved0;
-    uint32_t ticket_search;   // rounds of the search kernel that have finished
+    uint32_t ticket_search;   // rounds (or candidates) of the search that have finished
     uint32_t short_seq;       // 1: the search may drop the clamp of the rounded level
     uint32_t pad1;
     double b_e, b_r, step, F; // search grid: b_j = b_e + j*step, alpha_j = F*b_j
@@ -178,6 +178,62 @@ template <int DT> __device__ __forceinline__ void load16_stream(const void *base
 #define QP_TICKET_ACQUIRE() ((void)0)
 #endif
 
+// ---- device-coherent accesses ---------------------------------------------------------------
+// For data that blocks of one kernel hand to each other.  The L2 of an XCD is not coherent with
+// the other XCDs' for ordinary loads and stores; a device-scope release / acquire pair repairs
+// that by writing the whole L2 back and invalidating it, which costs microseconds per block.
+// Device-scope atomic accesses go to the point of coherence themselves, so a producer that
+// writes with st_dev, waits for its stores (wait_stores) and only then signals, and a consumer
+// that reads with ld_dev after seeing the signal, need no cache maintenance at all.
+__device__ __forceinline__ uint32_t ld_dev(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t ld_dev(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double ld_dev(const double *p)
+{
+    return __longlong_as_double((long long)ld_dev(reinterpret_cast<const uint64_t *>(p)));
+}
+__device__ __forceinline__ void st_dev(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(double *p, double v)
+{
+    st_dev(reinterpret_cast<uint64_t *>(p), (uint64_t)__double_as_longlong(v));
+}
+// all of this lane's outstanding memory operations (stores included) have been acknowledged
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ void st_dev(Part1 *dst, const Part1 &p)
+{
+    uint64_t *d = reinterpret_cast<uint64_t *>(dst);
+    st_dev(d, (uint64_t)__double_as_longlong(p.sum));
+    st_dev(d + 1, (uint64_t)__double_as_longlong(p.sum_abs));
+    st_dev(d + 2, (uint64_t)__float_as_uint(p.mn) | ((uint64_t)__float_as_uint(p.mx) << 32));
+    st_dev(d + 3, (uint64_t)p.bad);
+}
+__device__ __forceinline__ Part1 ld_dev(const Part1 *src)
+{
+    const uint64_t *s = reinterpret_cast<const uint64_t *>(src);
+    const uint64_t a = ld_dev(s), b = ld_dev(s + 1), c = ld_dev(s + 2), d = ld_dev(s + 3);
+    Part1 p;
+    p.sum = __longlong_as_double((long long)a);
+    p.sum_abs = __longlong_as_double((long long)b);
+    p.mn = __uint_as_float((uint32_t)c);
+    p.mx = __uint_as_float((uint32_t)(c >> 32));
+    p.bad = (uint32_t)d;
+    p.pad = 0u;
+    return p;
+}
+
 // ---- wave64 reductions -------------------------------------------------------------------
 // Four DPP steps (lane permutations inside a row of 16 lanes, executed in the vector ALU, no
 // LDS traffic) leave each row's result in all of its lanes; the four rows are then read with
@@ -278,13 +334,16 @@ constexpr int kFinThreads = 512;   // same block size as pass 2, so that both re
 
 // Sum of the pass-1 partials over one block of T lanes, in an order that depends only on T:
 // pass 2 (for mu, min, max) and the finalizer (for the record) get bit-identical values.
-template <int T>
+// DEV: the partials were written by other blocks of the same kernel (read them coherently).
+template <int T, bool DEV = false>
 __device__ __forceinline__ Part1 reduce_part1_block(const Part1 *__restrict__ part1, uint32_t nb1, Part1 *sh /*[T / 64]*/)
 {
     const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     Part1 t{0.0, 0.0, INFINITY, -INFINITY, 0u, 0u};
     for (uint32_t i = tid; i < nb1; i += T) {
-        const Part1 p = part1[i];
+        Part1 p;
+        if constexpr (DEV) p = ld_dev(part1 + i);
+        else p = part1[i];
         t.sum += p.sum;
         t.sum_abs += p.sum_abs;
         t.mn = fminf(t.mn, p.mn);
@@ -308,6 +367,32 @@ __device__ __forceinline__ Part1 reduce_part1_block(const Part1 *__restrict__ pa
         tot.bad += sh[w].bad;
     }
     return tot;
+}
+
+// The statistics record from the tensor-wide sums (Sec. 3: mu and b_E of the Laplace model, the
+// histogram's peak density and the bound b_R = 1 / (2 peak density) it gives).
+__device__ inline qp_stats_t stats_record(const Part1 &a, const Part2 &b, uint32_t pk, uint32_t nbins, uint64_t n)
+{
+    qp_stats_t st;
+    st.n = n;
+    st.n_nonfinite = a.bad;
+    st.mean = a.sum / (double)n;
+    st.mad = b.dev / (double)n;
+    st.abs_mean = a.sum_abs / (double)n;
+    st.var = b.sq / (double)n;
+    st.min = (double)a.mn;
+    st.max = (double)a.mx;
+    st.nbins = nbins;
+    st.peak_count = pk;
+    if (a.mx == a.mn) {   // one distinct value: the density peak is unbounded, the bound is 0
+        st.peak_density = 0.0;
+        st.b_r = 0.0;
+    } else {
+        const double binw = ((double)a.mx - (double)a.mn) / (double)nbins;
+        st.peak_density = (double)pk / ((double)n * binw);
+        st.b_r = 1.0 / (2.0 * st.peak_density);
+    }
+    return st;
 }
 
 __device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uint32_t nb1,
@@ -344,29 +429,53 @@ __device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uin
             b.sq += f2[w].sq;
             pk = max(pk, fpk[w]);
         }
-        qp_stats_t st;
-        st.n = n;
-        st.n_nonfinite = a.bad;
-        st.mean = a.sum / (double)n;
-        st.mad = b.dev / (double)n;
-        st.abs_mean = a.sum_abs / (double)n;
-        st.var = b.sq / (double)n;
-        st.min = (double)a.mn;
-        st.max = (double)a.mx;
-        st.nbins = nbins;
-        st.peak_count = pk;
-        if (a.mx == a.mn) {   // one distinct value: the density peak is unbounded, the bound is 0
-            st.peak_density = 0.0;
-            st.b_r = 0.0;
-        } else {
-            const double binw = ((double)a.mx - (double)a.mn) / (double)nbins;
-            st.peak_density = (double)pk / ((double)n * binw);
-            st.b_r = 1.0 / (2.0 * st.peak_density);
-        }
+        const qp_stats_t st = stats_record(a, b, pk, nbins, n);
         *out = st;
     }
     __syncthreads();   // the record is visible to the whole block from here on
 }
+
+// First minimum of scores[0 .. ncand) taken by one full wave: a candidate replaces the incumbent
+// only if its score is strictly lower, so ties keep the smaller index (b_E is kept unless
+// something is strictly better) and a NaN score never wins; a NaN incumbent (j = 0) is never
+// beaten.  Lanes scan j = lane, lane + 64, ... in ascending order, then a shuffle tree.  Every
+// lane returns the winner's index.
+__device__ __forceinline__ uint32_t first_min_wave(const double *scores, uint32_t ncand, uint32_t lane)
+{
+    double bs = INFINITY;
+    uint32_t bj = 0xffffffffu;
+    for (uint32_t j = lane; j < ncand; j += kWave) {
+        const double s = scores[j];
+        if (bj == 0xffffffffu || s < bs) {
+            bs = (s == s) ? s : INFINITY;
+            bj = j;
+        }
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const double os = __shfl_xor(bs, o, kWave);
+        const uint32_t oj = __shfl_xor(bj, o, kWave);
+        if (os < bs || (os == bs && oj < bj)) {
+            bs = os;
+            bj = oj;
+        }
+    }
+    const double s0 = scores[0];
+    if (!(s0 == s0)) bj = 0u;
+    return bj;
+}
+
+// What a search kernel needs to turn the partials of the statistics passes into the record itself
+// (the sender path launches no separate finalizer).
+struct FinalizeArgs {
+    const Part1 *part1;
+    const Part2 *part2;
+    const uint32_t *hist;
+    uint32_t nb1, nb2, nbins;   // nbins == 0: nothing to finalize
+};
+
+// Tensors of at most this many elements are searched with one candidate per lane.
+constexpr uint64_t kTileSearchMaxN = 1ull << 21;
 
 // The grid a clipping threshold induces; same statement as qp_make_qparams on the host.
 __device__ __host__ inline void make_grid(double center, double alpha, uint32_t bits, float &lo, float &hi,
@@ -405,6 +514,12 @@ uint32_t search_blocks(uint64_t n);
 hipError_t launch_hist_search(uint32_t bits, uint32_t t_steps, double F, void *ws, hipStream_t s);
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *host_qp,
                              const qp_qparams_t *dev_qp, void *packed, hipStream_t s);
+// The search with one candidate per lane over LDS-staged tiles, for tensors of at most
+// kTileSearchMaxN elements and at most 256 candidates (same arguments as launch_search).
+bool tile_search_eligible(uint64_t n, uint32_t t_steps);
+uint32_t tile_search_blocks(uint64_t n);
+hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, double F,
+                              const qp_stats_t *stats_host_or_null, uint32_t finalize_nbins, void *ws, hipStream_t s);
 hipError_t launch_unpack_dequant(const void *packed, uint32_t bits, const qp_qparams_t *host_qp,
                                  const qp_qparams_t *dev_qp, float *y, uint64_t n, hipStream_t s);
 

@@ -30,8 +30,8 @@ namespace qp {
 // weight counts[i].
 constexpr int kValues16 = 2;
 constexpr uint32_t kNumValues16 = 65536;
-// bf16 tensors at least this large are searched through their value table
-constexpr uint64_t kValueTableMinN = 1ull << 19;
+// bf16 tensors larger than the tile search takes are searched through their value table
+constexpr uint64_t kValueTableMinN = kTileSearchMaxN + 1;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
@@ -47,13 +47,6 @@ constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vect
 //
 // When the statistics passes have only left their partials (the fused sender path), this block
 // first turns them into the qp_stats_t record, which saves a launch.
-struct FinalizeArgs {
-    const Part1 *part1;
-    const Part2 *part2;
-    const uint32_t *hist;
-    uint32_t nb1, nb2, nbins;   // nbins == 0: nothing to finalize
-};
-
 __global__ __launch_bounds__(kFinThreads) void k_search_setup(qp_stats_t *__restrict__ stats_dev, double mean_h,
                                                               double b_e_h, double b_r_h, int from_ws, uint32_t bits,
                                                               uint32_t t_steps, double F, uint64_t n,
@@ -328,30 +321,9 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     if (!sh_flag || wave != 0) return;
     QP_TICKET_ACQUIRE();
 
-    // First minimum: a candidate replaces the incumbent only if its score is strictly lower, so
-    // ties keep the smaller index (b_E is kept unless something is strictly better) and a NaN
-    // score never wins.  Lanes scan j = lane, lane+64, ... in ascending order, then a shuffle tree.
-    double bs = INFINITY;
-    uint32_t bj = 0xffffffffu;
-    for (uint32_t j = lane; j < ncand; j += kWave) {
-        const double s = scores[j];
-        if (bj == 0xffffffffu || s < bs) {
-            bs = (s == s) ? s : INFINITY;
-            bj = j;
-        }
-    }
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) {
-        const double os = __shfl_xor(bs, o, kWave);
-        const uint32_t oj = __shfl_xor(bj, o, kWave);
-        if (os < bs || (os == bs && oj < bj)) {
-            bs = os;
-            bj = oj;
-        }
-    }
+    const uint32_t bj = first_min_wave(scores, ncand, lane);
     if (lane == 0) {
         const double s0 = scores[0];
-        if (!(s0 == s0)) bj = 0u;   // a NaN incumbent is never beaten
         const double sbest = scores[bj];
         qp_search_result_t r;
         r.b_e = ctl->b_e;
@@ -420,27 +392,9 @@ __global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__
     if (!sh_flag || wave != 0) return;
     QP_TICKET_ACQUIRE();
 
-    double bs = INFINITY;
-    uint32_t bj = 0xffffffffu;
-    for (uint32_t k = lane; k < ncand; k += kWave) {
-        const double v = scores[k];
-        if (bj == 0xffffffffu || v < bs) {
-            bs = (v == v) ? v : INFINITY;
-            bj = k;
-        }
-    }
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) {
-        const double os = __shfl_xor(bs, o, kWave);
-        const uint32_t oj = __shfl_xor(bj, o, kWave);
-        if (os < bs || (os == bs && oj < bj)) {
-            bs = os;
-            bj = oj;
-        }
-    }
+    const uint32_t bj = first_min_wave(scores, ncand, lane);
     if (lane == 0) {
         const double s0 = scores[0];
-        if (!(s0 == s0)) bj = 0u;
         qp_search_result_t r;
         r.b_e = b_e;
         r.b_r = b_r;
@@ -543,6 +497,8 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
 hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
                          double F, const qp_stats_t *st, uint32_t finalize_nbins, void *ws, hipStream_t s)
 {
+    // small and medium tensors: one candidate per lane over LDS tiles
+    if (tile_search_eligible(n, t_steps)) return launch_tile_search(x, n, dtype, bits, t_steps, F, st, finalize_nbins, ws, s);
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);

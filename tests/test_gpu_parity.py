@@ -168,8 +168,8 @@ def test_aciq_alpha_matches_oracle(qp):
 
 SEARCH_CASES = [("C1", None, (2, 4, 8)), ("C2", 300_007, BITS), ("C3", 250_001, (2, 4, 8)),
                 ("C4", 200_000, (2, 6, 16)), ("C5", 300_011, (2, 3, 4, 8)),
-                # bf16 tensors of 2^19 elements or more are searched through their value table
-                ("C5", 1_000_003, (2, 3, 8))]
+                # large bf16 tensors are searched through their value table
+                ("C5", 2_500_003, (2, 8))]
 
 
 @pytest.mark.parametrize("name,n,bitset", SEARCH_CASES, ids=[f"{c[0]}_{c[1]}" for c in SEARCH_CASES])
@@ -584,27 +584,141 @@ def test_largest_supported_tensor(qp):
 
 # ----------------------------------------------------------------------------- sender path on edge cases, graphs, streams
 
-@pytest.mark.parametrize("name,x", si.edge_cases(), ids=[c[0] for c in si.edge_cases()])
-def test_fused_sender_path_on_edge_cases(qp, name, x):
-    """qp_compress_async (statistics finalized inside the search set-up) equals the step-by-step path."""
-    xd = to_dev(x)
+def check_sender_result(qp, x, bits, ws, packed, t_steps=100, nbins=2048):
+    """A finished qp_compress_async call against the oracle: statistics and histogram, the scores of
+    all candidates (oracle given the GPU's statistics), the winner, and the packed stream (oracle
+    given the GPU's grid)."""
+    xf = as_f32(x)
     n = x.size
-    for bits in (2, 6):
-        ws = qp.alloc_workspace(n)
-        st = qp.qp_stats(xd, ws)
-        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
-        p_ref = qp.alloc_packed(n, bits)
-        qp.qp_quant_pack(xd, q, p_ref)
-        ws2 = qp.alloc_workspace(n)
-        ws2.fill_(0xC3)
-        p_dev = qp.alloc_packed(n, bits)
-        qp.qp_compress_async(xd, bits, ws2, p_dev)
+    st = qp.read_ws(ws, qp.QP_WS_STATS, qp.qp_stats_t)
+    rc, ref, hist_ref = orc.stats(xf, nbins=nbins, want_hist=True)
+    assert rc == 0 and st.n == ref.n == n and st.n_nonfinite == 0
+    assert (st.min, st.max, st.nbins, st.peak_count) == (ref.min, ref.max, nbins, ref.peak_count)
+    for f in ("mean", "mad", "abs_mean", "var"):
+        a, b = getattr(st, f), getattr(ref, f)
+        scale = max(abs(b), ref.abs_mean * 1e-3 if f == "mean" else 0.0)
+        assert abs(a - b) <= REL_STATS * scale, (f, a, b)
+    off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    hist = ws[off:off + 4 * nbins].cpu().numpy().view(np.uint32)
+    assert np.array_equal(hist, hist_ref[:nbins])
+    assert st.b_r == pytest.approx(ref.b_r, rel=1e-14) and st.peak_density == pytest.approx(ref.peak_density, rel=1e-14)
+    res = qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)
+    q = qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    scores = ws[off:off + 8 * (t_steps + 1)].cpu().numpy().view(np.float64)
+    ores, oq, oscores = orc.dsaciq_search(xf, oracle_stats_from(st), bits, t_steps)
+    # from about 10^6 terms on, the oracle's term-by-term sum is itself off by ~1e-11: the pairwise sum is the tight check
+    tol = REL_SCORE if n < (1 << 19) else REL_SCORE_FULL
+    assert np.allclose(scores, oscores, rtol=tol, atol=0.0, equal_nan=True)
+    if n >= (1 << 19):
+        for j in (0, t_steps // 3, t_steps):
+            oqj = orc.make_qparams(st.mean, orc.laplace_F(bits) * (ores.b_e + j * ((ores.b_r - ores.b_e) / t_steps)), bits, n)
+            assert scores[j] == pytest.approx(pairwise_sq_error(xf, oqj), rel=REL_SCORE_PAIRWISE)
+    assert res.t_steps == t_steps and (res.b_e, res.b_r) == (ores.b_e, ores.b_r)
+    if res.j_star != ores.j_star:   # only an exact numerical tie may differ
+        assert abs(oscores[res.j_star] - oscores[ores.j_star]) <= 1e-12 * oscores[ores.j_star]
+        oq = orc.make_qparams(st.mean, res.alpha_star, bits, n)
+    else:
+        assert res.alpha_star == pytest.approx(ores.alpha_star, rel=1e-14)
+        assert res.mse_star == pytest.approx(ores.mse_star, rel=tol, nan_ok=True)
+    assert res.mse_aciq == pytest.approx(ores.mse_aciq, rel=tol, nan_ok=True)
+    assert (q.bits, q.n, q.lo, q.hi, q.scale, q.inv_scale) == (bits, n, oq.lo, oq.hi, oq.scale, oq.inv_scale)
+    assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(xf, oracle_q_from(q)), bits))
+    return st, res, q
+
+
+@pytest.mark.parametrize("name,x", si.edge_cases(), ids=[c[0] for c in si.edge_cases()])
+def test_sender_path_on_edge_cases(qp, name, x):
+    """qp_compress_async on the edge cases, fp32 and bf16: against the oracle, and bit for bit against
+    the step-by-step calls (which run the same kernels, with the statistics finalized separately)."""
+    for xin in (x, si.f32_to_bf16_bits(x)):
+        xd = to_dev(xin)
+        n = xin.size
+        for bits in (2, 6):
+            print(f"[case] sender {name} {xin.dtype} n={n} bits={bits}", flush=True)
+            ws = qp.alloc_workspace(n)
+            ws.fill_(0xC3)                              # the workspace needs no initialisation
+            packed = qp.alloc_packed(n, bits)
+            packed.fill_(0x77)
+            qp.qp_compress_async(xd, bits, ws, packed)
+            torch.cuda.synchronize()
+            st, res, q = check_sender_result(qp, xin, bits, ws, packed)
+            ws2 = qp.alloc_workspace(n)
+            st2 = qp.qp_stats(xd, ws2)
+            res2, q2 = qp.qp_dsaciq_search(xd, st2, bits, ws2)
+            p2 = qp.alloc_packed(n, bits)
+            qp.qp_quant_pack(xd, q2, p2)
+            assert bytes(st) == bytes(st2) and bytes(q) == bytes(q2) and torch.equal(packed, p2)
+            assert bytes(res) == bytes(res2) or (np.isnan(res2.mse_star) and res.j_star == res2.j_star)
+
+
+SENDER_CASES = [("C1", None, BITS), ("C5", 151_296, BITS), ("C2", 605_187, (3, 8)), ("C3", 1_048_576, (4, 16)), ("C2", 2_097_152, (4,)),
+                    ("C4", 77_773, (2, 6)), ("C5", 999_999, (2, 3))]
+
+
+@pytest.mark.parametrize("name,n,bitset", SENDER_CASES, ids=[f"{c[0]}_{c[1]}" for c in SENDER_CASES])
+def test_sender_path_matches_oracle(qp, name, n, bitset):
+    """qp_compress_async on small and medium tensors (searched with one candidate per lane): every
+    intermediate it leaves in the workspace is checked."""
+    x = si.make_config(name, n=n)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    qrec = torch.zeros(32, dtype=torch.uint8, device="cuda")
+    for bits in bitset:
+        print(f"[case] sender {name} n={x.size} bits={bits}", flush=True)
+        packed = qp.alloc_packed(x.size, bits)
+        qp.qp_compress_async(xd, bits, ws, packed, qparams_out_dev_ptr=qrec.data_ptr())
         torch.cuda.synchronize()
-        assert bytes(qp.read_ws(ws2, qp.QP_WS_STATS, qp.qp_stats_t)) == bytes(st)
-        assert bytes(qp.read_ws(ws2, qp.QP_WS_QPARAMS, qp.qp_qparams_t)) == bytes(q)
-        r2 = qp.read_ws(ws2, qp.QP_WS_RESULT, qp.qp_search_result_t)
-        assert bytes(r2) == bytes(res) or (np.isnan(res.mse_star) and r2.j_star == res.j_star)
-        assert torch.equal(p_ref, p_dev)
+        st, res, q = check_sender_result(qp, x, bits, ws, packed)
+        assert bytes(qrec.cpu().numpy().tobytes()) == bytes(q)
+        y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant_dev(packed, bits, qrec.data_ptr(), y)
+        oq = oracle_q_from(q)
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(orc.quantize(as_f32(x), oq), oq))
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 127, 128, 129, 511, 513, 4095, 4097, 32_768, 65_537, 262_147, 1_048_575, 2_097_151])
+def test_sender_path_sizes(qp, n):
+    x = si.unit_laplace(n, seed=n) * np.float32(0.7) + np.float32(0.1)
+    xd = to_dev(x)
+    for bits in (3, 4):
+        print(f"[case] sender size n={n} bits={bits}", flush=True)
+        ws = qp.alloc_workspace(n)
+        ws.fill_(0x3C)
+        packed = qp.alloc_packed(n, bits)
+        qp.qp_compress_async(xd, bits, ws, packed)
+        torch.cuda.synchronize()
+        check_sender_result(qp, x, bits, ws, packed)
+
+
+def test_sender_path_other_grids(qp):
+    x = si.make_config("C2", n=200_003)
+    xd = to_dev(x)
+    for t, nbins in ((1, 2048), (10, 16), (100, 4096), (255, 100)):
+        cfg = qp.qp_default_search_cfg()
+        cfg.t_steps, cfg.nbins = t, nbins
+        ws = qp.alloc_workspace(x.size, cfg)
+        packed = qp.alloc_packed(x.size, 4)
+        print(f"[case] sender t={t} nbins={nbins}", flush=True)
+        qp.qp_compress_async(xd, 4, ws, packed, cfg=cfg)
+        torch.cuda.synchronize()
+        check_sender_result(qp, x, 4, ws, packed, t_steps=t, nbins=nbins)
+
+
+def test_sender_path_is_bit_reproducible(qp):
+    x = si.make_config("C1")
+    xd = to_dev(x)
+    outs = []
+    for rep in range(4):
+        ws = qp.alloc_workspace(x.size)
+        ws.fill_(rep * 37 + 1)
+        packed = qp.alloc_packed(x.size, 3)
+        qp.qp_compress_async(xd, 3, ws, packed)
+        torch.cuda.synchronize()
+        off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+        outs.append((bytes(qp.read_ws(ws, qp.QP_WS_STATS, qp.qp_stats_t)), bytes(qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)),
+                     ws[off:off + 8 * 101].cpu().numpy().tobytes(), packed.cpu().numpy().tobytes()))
+    assert all(o == outs[0] for o in outs[1:])
 
 
 def test_sender_and_receiver_replay_from_a_hip_graph(qp):
@@ -727,7 +841,7 @@ def test_hist_search_degenerate_inputs(qp, name):
 @pytest.mark.parametrize("kind", ["constant", "two_point", "ramp_of_all_patterns", "laplace_ragged"])
 def test_bf16_value_table_search_edge_cases(qp, kind):
     """Large bf16 tensors are searched through the table of their (at most 65536) distinct values."""
-    n = (1 << 19) + 13
+    n = (1 << 21) + 13
     rng = np.random.default_rng(17)
     if kind == "constant":
         x = np.full(n, 0.75, np.float32)
