@@ -197,6 +197,9 @@ def main() -> int:
         torch.cuda.empty_cache()
         large = large_tensor_leg(qp, si, torch, timed_reps, args.kernel_reps)
 
+    # one image's activations (1x197x768 fp32): the whole sender path per tensor, launch-bound
+    small = small_tensor_leg(qp, si, torch, timed_reps)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(x_host, bits_set)
@@ -216,6 +219,7 @@ def main() -> int:
         "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
         "per_bitwidth": per_bits,
         "large_tensor_bf16": large,
+        "small_tensor_fp32": small,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -247,6 +251,21 @@ def large_tensor_leg(qp, si, torch, timed_reps, reps):
             out["dsaciq_us_per_tensor"] = ts
         del packs
     return out
+
+
+def small_tensor_leg(qp, si, torch, timed_reps):
+    """Sender path (statistics, DS-ACIQ t = 100, quantize+pack) and its search alone on the 1x197x768 tensor."""
+    x = si.make_config("C1")
+    n = x.size
+    nb = 4
+    xs = [torch.from_numpy(x).cuda() for _ in range(nb)]
+    ws = qp.alloc_workspace(n)
+    packed = qp.alloc_packed(n, 4)
+    qp.qp_stats(xs[0], ws)
+    t_search = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], 4, ws))
+    t_send = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], 4, ws, packed))
+    return {"elements": n, "bits": 4, "dsaciq_us_per_tensor": t_search, "sender_path_us_per_tensor": t_send,
+            "timed": "back-to-back calls on one stream between two HIP events"}
 
 
 def cpu_baseline(x_host, bits_set):

@@ -475,7 +475,10 @@ struct FinalizeArgs {
 };
 
 // Tensors of at most this many elements are searched with one candidate per lane.
-constexpr uint64_t kTileSearchMaxN = 1ull << 21;
+#ifndef QP_TILE_SEARCH_MAX_N
+#define QP_TILE_SEARCH_MAX_N (1ull << 21)
+#endif
+constexpr uint64_t kTileSearchMaxN = QP_TILE_SEARCH_MAX_N;
 
 // The grid a clipping threshold induces; same statement as qp_make_qparams on the host.
 __device__ __host__ inline void make_grid(double center, double alpha, uint32_t bits, float &lo, float &hi,

@@ -30,8 +30,9 @@ namespace qp {
 // weight counts[i].
 constexpr int kValues16 = 2;
 constexpr uint32_t kNumValues16 = 65536;
-// bf16 tensors larger than the tile search takes are searched through their value table
-constexpr uint64_t kValueTableMinN = kTileSearchMaxN + 1;
+// bf16 tensors at least this large are searched through their value table (counting the values and
+// searching 65536 of them costs about 30 us; the tile search passes that at about a million elements)
+constexpr uint64_t kValueTableMinN = 1ull << 20;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
@@ -497,8 +498,12 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
 hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
                          double F, const qp_stats_t *st, uint32_t finalize_nbins, void *ws, hipStream_t s)
 {
-    // small and medium tensors: one candidate per lane over LDS tiles
-    if (tile_search_eligible(n, t_steps)) return launch_tile_search(x, n, dtype, bits, t_steps, F, st, finalize_nbins, ws, s);
+    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
+    // them once (one pass over the tensor) and run the candidates over the value table.
+    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
+    // other small and medium tensors: one candidate per lane over LDS tiles
+    if (!by_values && tile_search_eligible(n, t_steps))
+        return launch_tile_search(x, n, dtype, bits, t_steps, F, st, finalize_nbins, ws, s);
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
@@ -508,9 +513,6 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
     FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                      reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
     if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
-    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
-    // them once (one pass over the tensor) and run the candidates over the value table.
-    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
     uint32_t *value_counts = reinterpret_cast<uint32_t *>(w + kOffValueCounts);
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, stats_dev, st ? st->mean : 0.0,
                        st ? st->mad : 0.0, st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets,

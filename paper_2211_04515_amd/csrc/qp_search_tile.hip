@@ -29,7 +29,7 @@ constexpr int kStThreads = kFinThreads;          // 512: finalize_stats_block fi
 constexpr uint32_t kStVecs = 2;                  // 4-element vectors a lane stages per sub-tile
 constexpr uint32_t kStSub = kStThreads * kStVecs * 4;   // 4096 elements per sub-tile (16 KB of LDS)
 constexpr uint32_t kStMaxCands = 256;            // every candidate gets a lane (or several)
-constexpr uint32_t kStMaxBlocks = 512;
+constexpr uint32_t kStMaxBlocks = 256;              // one block per compute unit: no unit gets two while others idle
 
 struct TileSearchArgs {
     const void *x;

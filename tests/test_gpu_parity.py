@@ -169,7 +169,7 @@ def test_aciq_alpha_matches_oracle(qp):
 SEARCH_CASES = [("C1", None, (2, 4, 8)), ("C2", 300_007, BITS), ("C3", 250_001, (2, 4, 8)),
                 ("C4", 200_000, (2, 6, 16)), ("C5", 300_011, (2, 3, 4, 8)),
                 # large bf16 tensors are searched through their value table
-                ("C5", 2_500_003, (2, 8))]
+                ("C5", 1_200_003, (2, 8))]
 
 
 @pytest.mark.parametrize("name,n,bitset", SEARCH_CASES, ids=[f"{c[0]}_{c[1]}" for c in SEARCH_CASES])
@@ -653,7 +653,7 @@ def test_sender_path_on_edge_cases(qp, name, x):
 
 
 SENDER_CASES = [("C1", None, BITS), ("C5", 151_296, BITS), ("C2", 605_187, (3, 8)), ("C3", 1_048_576, (4, 16)), ("C2", 2_097_152, (4,)),
-                    ("C4", 77_773, (2, 6)), ("C5", 999_999, (2, 3))]
+                    ("C4", 77_773, (2, 6)), ("C5", 999_999, (2, 3)), ("C5", 1_300_001, (4,))]
 
 
 @pytest.mark.parametrize("name,n,bitset", SENDER_CASES, ids=[f"{c[0]}_{c[1]}" for c in SENDER_CASES])
@@ -841,7 +841,7 @@ def test_hist_search_degenerate_inputs(qp, name):
 @pytest.mark.parametrize("kind", ["constant", "two_point", "ramp_of_all_patterns", "laplace_ragged"])
 def test_bf16_value_table_search_edge_cases(qp, kind):
     """Large bf16 tensors are searched through the table of their (at most 65536) distinct values."""
-    n = (1 << 21) + 13
+    n = (1 << 20) + 13
     rng = np.random.default_rng(17)
     if kind == "constant":
         x = np.full(n, 0.75, np.float32)
