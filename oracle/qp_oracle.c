@@ -21,7 +21,11 @@
  * constant against a brute-force minimum of numerically integrated noise; the
  * search against an independent numpy sweep on tiny tensors; quantize against
  * invariants and the 8-bit identity; pack/unpack against numpy.packbits and
- * uint8/uint16 views; dequantize against the fp64 definition.
+ * uint8/uint16 views; dequantize against the fp64 definition; the search variants
+ * (Gaussian model, range intersected with the data's, coarse-to-fine sweep) against
+ * the paper's search at their defaults, an independent numpy sweep, a hand-worked
+ * grid, an exact normal histogram, and (the sweep's index logic) the plain argmin of
+ * unimodal curves.
  */
 #include <math.h>
 #include <stddef.h>
@@ -420,5 +424,145 @@ int orc_hist_search(const orc_stats_t *st, const uint32_t *hist, uint32_t bits, 
     res->mse_aciq = first / (double)B;
     res->mse_star = best / (double)B;
     if (best_q) orc_make_qparams(st->mean, res->alpha_star, bits, st->n, best_q);
+    return 0;
+}
+
+/* ---- Variants of the directed search (beyond the paper's method) ----------------
+ *
+ * The paper models activations as Laplace and clips symmetrically about mu (Sec. 3).
+ * Three variations on Eq. 1 that keep its structure (candidates on a straight grid of scale
+ * values from the moment estimate to the bound given by the histogram peak, scored by the
+ * quantization error on the real tensor, first minimum wins):
+ *
+ *   dist = ORC_GAUSS   the Gaussian model of the cited ACIQ method: scale estimate
+ *                      sigma_E = sqrt(var), threshold alpha = G(q) sigma, and the bound is the
+ *                      sigma whose density peak 1/(sigma sqrt(2 pi)) equals the histogram's:
+ *                      sigma_R = 1 / (sqrt(2 pi) max D_R).
+ *   clip_to_data       the clipping range is intersected with the data's own range,
+ *                      [max(mu - alpha, min), min(mu + alpha, max)]: one-sided data (after a
+ *                      GELU, say) then spends no levels below its minimum.
+ *   stride > 1         coarse-to-fine sweep: first the candidates j = 0, s, 2s, ... and t; then all
+ *                      candidates within s - 1 of the coarse winner j1.  The result is the first
+ *                      minimum of the second sweep (which contains j1; no other coarse candidate
+ *                      can beat or tie it at a smaller index).  On a curve that falls to its
+ *                      minimum and rises after it this is the full sweep's answer with about
+ *                      t/s + 2s evaluations instead of t + 1.  scores[] entries that were never
+ *                      evaluated are NaN.
+ * With dist = ORC_LAPLACE, clip_to_data = 0 and stride = 1 this is orc_dsaciq_search.
+ */
+int orc_make_qparams_clipped(double center, double alpha, double data_min, double data_max, uint32_t bits,
+                             uint64_t n, orc_qparams_t *q)
+{
+    int rc = orc_make_qparams(center, alpha, bits, n, q);
+    if (rc) return rc;
+    float mn = (float)data_min, mx = (float)data_max;
+    if (q->lo < mn) q->lo = mn;
+    if (q->hi > mx) q->hi = mx;
+    double range = (double)q->hi - (double)q->lo;
+    if (!(q->hi > q->lo)) {
+        q->scale = 0.0f;
+        q->inv_scale = 0.0f;
+    } else {
+        q->scale = (float)(range / (double)q->levels);
+        q->inv_scale = (float)((double)q->levels / range);
+    }
+    return 0;
+}
+
+/* a NaN score never wins a comparison: it counts as +infinity */
+static double orc_key(double s) { return s == s ? s : INFINITY; }
+
+/* which candidate a coarse-to-fine sweep picks if the full score table were `scores` (only the
+ * entries the sweep would evaluate are read); evaluated[j] is set for those, if given */
+uint32_t orc_c2f_pick(const double *scores, uint32_t t_steps, uint32_t stride, uint8_t *evaluated)
+{
+    if (evaluated) memset(evaluated, 0, (size_t)t_steps + 1);
+    uint32_t j1 = 0;
+    double best = 0.0;
+    for (uint32_t i = 0;; ++i) {                      /* coarse sweep: 0, s, 2s, ..., t */
+        uint64_t jj = (uint64_t)i * stride;
+        uint32_t j = jj > t_steps ? t_steps : (uint32_t)jj;
+        if (evaluated) evaluated[j] = 1;
+        if (i == 0 || scores[j] < best) { best = orc_key(scores[j]); j1 = j; }
+        if (j == t_steps) break;
+    }
+    uint32_t from = j1 >= stride - 1 ? j1 - (stride - 1) : 0;
+    uint32_t to = (uint64_t)j1 + stride - 1 > t_steps ? t_steps : j1 + stride - 1;
+    uint32_t j2 = from;
+    for (uint32_t j = from; j <= to; ++j) {           /* fine sweep around the coarse winner */
+        if (evaluated) evaluated[j] = 1;
+        if (j == from || scores[j] < best) { best = orc_key(scores[j]); j2 = j; }
+    }
+    if (!(scores[0] == scores[0])) j2 = 0;             /* a NaN incumbent is never beaten */
+    return j2;
+}
+
+int orc_dsaciq_search_variant(const float *x, uint64_t n, const orc_stats_t *st, uint32_t bits, uint32_t t_steps,
+                              int dist, int clip_to_data, uint32_t stride, orc_search_result_t *res,
+                              orc_qparams_t *best_q, double *scores /* t_steps + 1 */)
+{
+    if (!orc_bits_ok(bits) || t_steps == 0 || n == 0 || stride == 0 || !scores) return 2;
+    double C, s_e, s_r;
+    if (dist == ORC_LAPLACE) {
+        C = orc_laplace_F(bits);
+        s_e = st->mad;
+        s_r = st->b_r;
+    } else if (dist == ORC_GAUSS) {
+        C = orc_gauss_G(bits);
+        s_e = sqrt(st->var);
+        s_r = 1.0 / (sqrt(2.0 * 3.14159265358979323846) * st->peak_density);
+        if (st->peak_density == 0.0) s_r = 0.0;        /* one distinct value: same convention as b_R */
+    } else {
+        return 2;
+    }
+    double step = (s_r - s_e) / (double)t_steps;
+    if (!(s_e > 0.0) || !(s_r > 0.0) || !isfinite(s_r) || !isfinite(s_e) || !isfinite(step)) step = 0.0;
+    /* evaluate lazily: exactly the candidates the sweep asks for (NaN marks "not evaluated"; a score
+     * that is really NaN is merely computed again) */
+    for (uint32_t j = 0; j <= t_steps; ++j) scores[j] = NAN;
+#define ORC_EVAL(j)                                                                                         \
+    do {                                                                                                    \
+        if (!(scores[(j)] == scores[(j)])) {                                                                \
+            orc_qparams_t q_;                                                                               \
+            double a_ = C * (s_e + (double)(j) * step);                                                     \
+            if (clip_to_data) orc_make_qparams_clipped(st->mean, a_, st->min, st->max, bits, n, &q_);       \
+            else orc_make_qparams(st->mean, a_, bits, n, &q_);                                              \
+            scores[(j)] = orc_sq_error(x, n, &q_);                                                          \
+        }                                                                                                   \
+    } while (0)
+    uint32_t j1 = 0, j_star;
+    double best = 0.0;
+    for (uint32_t i = 0;; ++i) {
+        uint64_t jj = (uint64_t)i * stride;
+        uint32_t j = jj > t_steps ? t_steps : (uint32_t)jj;
+        ORC_EVAL(j);
+        if (i == 0 || scores[j] < best) { best = orc_key(scores[j]); j1 = j; }
+        if (j == t_steps) break;
+    }
+    j_star = j1;
+    if (stride > 1) {
+        uint32_t from = j1 >= stride - 1 ? j1 - (stride - 1) : 0;
+        uint32_t to = (uint64_t)j1 + stride - 1 > t_steps ? t_steps : j1 + stride - 1;
+        j_star = from;
+        for (uint32_t j = from; j <= to; ++j) {
+            ORC_EVAL(j);
+            if (j == from || scores[j] < best) { best = orc_key(scores[j]); j_star = j; }
+        }
+    }
+#undef ORC_EVAL
+    if (!(scores[0] == scores[0])) j_star = 0;
+    double s_star = s_e + (double)j_star * step;
+    res->b_e = s_e;
+    res->b_r = s_r;
+    res->b_star = s_star;
+    res->alpha_star = C * s_star;
+    res->j_star = j_star;
+    res->t_steps = t_steps;
+    res->mse_aciq = scores[0] / (double)n;
+    res->mse_star = scores[j_star] / (double)n;
+    if (best_q) {
+        if (clip_to_data) orc_make_qparams_clipped(st->mean, res->alpha_star, st->min, st->max, bits, n, best_q);
+        else orc_make_qparams(st->mean, res->alpha_star, bits, n, best_q);
+    }
     return 0;
 }

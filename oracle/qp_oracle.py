@@ -89,6 +89,14 @@ def lib():
         L.orc_hist_search.restype = C.c_int
         L.orc_next_bits.argtypes = [C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_uint32)]
         L.orc_next_bits.restype = C.c_int
+        L.orc_make_qparams_clipped.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint32, C.c_uint64,
+                                               C.POINTER(QParams)]
+        L.orc_make_qparams_clipped.restype = C.c_int
+        L.orc_c2f_pick.argtypes = [dp, C.c_uint32, C.c_uint32, u8p]
+        L.orc_c2f_pick.restype = C.c_uint32
+        L.orc_dsaciq_search_variant.argtypes = [fp, C.c_uint64, C.POINTER(Stats), C.c_uint32, C.c_uint32, C.c_int, C.c_int,
+                                                C.c_uint32, C.POINTER(SearchResult), C.POINTER(QParams), dp]
+        L.orc_dsaciq_search_variant.restype = C.c_int
         _lib = L
     return _lib
 
@@ -231,4 +239,39 @@ def hist_search(st, hist, bits, t_steps=100):
                                scores.ctypes.data_as(C.POINTER(C.c_double)))
     if rc:
         raise ValueError("orc_hist_search: bad argument")
+    return res, q, scores
+
+
+# ---- variants of the directed search (not the paper's method; see the C source) -------------------
+
+LAPLACE, GAUSS = 0, 1
+
+
+def make_qparams_clipped(center, alpha, data_min, data_max, bits, n):
+    q = QParams()
+    rc = lib().orc_make_qparams_clipped(float(center), float(alpha), float(data_min), float(data_max), int(bits), int(n),
+                                        C.byref(q))
+    if rc:
+        raise ValueError("orc_make_qparams_clipped: bad bitwidth")
+    return q
+
+
+def c2f_pick(scores, stride):
+    """(index a coarse-to-fine sweep with this stride picks from a full score table, mask of the entries it reads)."""
+    sc = np.ascontiguousarray(scores, dtype=np.float64)
+    ev = np.zeros(sc.size, dtype=np.uint8)
+    j = lib().orc_c2f_pick(sc.ctypes.data_as(C.POINTER(C.c_double)), sc.size - 1, int(stride),
+                           ev.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return int(j), ev.astype(bool)
+
+
+def dsaciq_search_variant(x, st, bits, t_steps=100, dist=LAPLACE, clip_to_data=False, stride=1):
+    """Returns (SearchResult, QParams of the winner, scores[t+1] with NaN where nothing was evaluated)."""
+    a, p = _f32(x)
+    res, q = SearchResult(), QParams()
+    scores = np.zeros(t_steps + 1, dtype=np.float64)
+    rc = lib().orc_dsaciq_search_variant(p, a.size, C.byref(st), int(bits), int(t_steps), int(dist), int(bool(clip_to_data)),
+                                         int(stride), C.byref(res), C.byref(q), scores.ctypes.data_as(C.POINTER(C.c_double)))
+    if rc:
+        raise ValueError("orc_dsaciq_search_variant: bad argument")
     return res, q, scores

@@ -529,3 +529,151 @@ def test_hist_search_degenerate_keeps_b_e():
     st.mad = 0.5          # pretend a scale; the bound is 0, so the grid collapses
     res, q, scores = orc.hist_search(st, hist, 4, 50)
     assert res.j_star == 0 and res.b_star == 0.5
+
+
+# ----------------------------------------------------------------------------- variants of the search
+# (Gaussian model, range intersected with the data's, coarse-to-fine sweep: not the paper's method)
+
+def test_variant_with_defaults_is_the_papers_search():
+    for name, bits in (("C1", 2), ("C3", 4), ("C2", 8)):
+        x = si.make_config(name, n=6000)
+        rc, st = orc.stats(x)
+        r0, q0, s0 = orc.dsaciq_search(x, st, bits, 50)
+        r1, q1, s1 = orc.dsaciq_search_variant(x, st, bits, 50)
+        assert bytes(r0) == bytes(r1) and bytes(q0) == bytes(q1) and np.array_equal(s0, s1)
+
+
+def test_clipped_grid_hand_worked_and_special_cases():
+    # centre 1, alpha 2 -> [-1, 3]; data in [0, 10] -> [0, 3]; 2 bits: 3 intervals of width 1
+    q = orc.make_qparams_clipped(1.0, 2.0, 0.0, 10.0, 2, 7)
+    assert (q.lo, q.hi, q.scale, q.inv_scale, q.levels, q.n) == (0.0, 3.0, 1.0, 1.0, 3, 7)
+    # data on both sides inside the range: both ends move
+    q = orc.make_qparams_clipped(0.0, 8.0, -1.5, 6.0, 4, 1)
+    assert (q.lo, q.hi) == (-1.5, 6.0) and q.scale == np.float32(7.5 / 15)
+    # data range wider than the clipping range: nothing changes
+    for bits in (2, 8):
+        a = orc.make_qparams(0.3, 1.7, bits, 5)
+        b = orc.make_qparams_clipped(0.3, 1.7, -100.0, 100.0, bits, 5)
+        assert bytes(a) == bytes(b)
+    # one distinct value: empty range, all codes 0
+    q = orc.make_qparams_clipped(2.0, 1.0, 2.0, 2.0, 4, 3)
+    assert (q.lo, q.hi, q.scale, q.inv_scale) == (2.0, 2.0, 0.0, 0.0)
+
+
+def _numpy_scores_variant(x, mean, s_e, s_r, const, bits, t, lo_clip, hi_clip):
+    """Independent sweep with numpy float32/float64 operations; the range is intersected with [lo_clip, hi_clip]."""
+    L = 2 ** bits - 1
+    scores = []
+    for j in range(t + 1):
+        s = s_e + j * ((s_r - s_e) / t)
+        a32, c32 = np.float32(const * s), np.float32(mean)
+        lo = max(np.float32(np.float64(c32) - np.float64(a32)), np.float32(lo_clip))
+        hi = min(np.float32(np.float64(c32) + np.float64(a32)), np.float32(hi_clip))
+        rng_ = np.float64(hi) - np.float64(lo)
+        scale, inv = np.float32(rng_ / L), np.float32(L / rng_)
+        r = np.clip(np.rint((np.minimum(np.maximum(x, lo), hi) - lo) * inv), 0, L)
+        xh = (np.float64(lo) + r.astype(np.float64) * np.float64(scale)).astype(np.float32)
+        e = (x - xh).astype(np.float64)
+        scores.append(float(np.sum(e * e)))
+    return np.array(scores)
+
+
+@pytest.mark.parametrize("name,bits,dist,clip", [("C3", 2, 0, True), ("C3", 4, 0, True), ("C2", 3, 1, False),
+                                                 ("C1", 4, 1, False), ("C3", 8, 1, True), ("C2", 2, 0, True)])
+def test_variant_matches_brute_force_numpy_sweep(name, bits, dist, clip):
+    x = si.make_config(name, n=4096)
+    rc, st = orc.stats(x)
+    res, q, scores = orc.dsaciq_search_variant(x, st, bits, 60, dist=dist, clip_to_data=clip)
+    if dist == orc.GAUSS:
+        # Gaussian model: sigma from the variance; bound = sigma of the normal density with the histogram's peak
+        const = orc.gauss_G(bits)
+        s_e, s_r = np.sqrt(st.var), 1.0 / (np.sqrt(2 * np.pi) * st.peak_density)
+    else:
+        const = scipy.special.lambertw(3.0 * 4.0 ** bits).real
+        s_e, s_r = st.mad, st.b_r
+    assert (res.b_e, res.b_r) == (pytest.approx(s_e, rel=1e-15), pytest.approx(s_r, rel=1e-15))
+    lo_clip, hi_clip = (st.min, st.max) if clip else (-np.inf, np.inf)
+    ref = _numpy_scores_variant(x, st.mean, s_e, s_r, const, bits, 60, lo_clip, hi_clip)
+    assert np.allclose(scores, ref, rtol=1e-6, atol=0)
+    assert res.j_star == int(np.argmin(scores))
+    assert res.alpha_star == pytest.approx(const * (s_e + res.j_star * ((s_r - s_e) / 60)), rel=1e-13)
+    if clip:
+        assert q.lo >= np.float32(st.min) and q.hi <= np.float32(st.max)
+        assert bytes(q) == bytes(orc.make_qparams_clipped(st.mean, res.alpha_star, st.min, st.max, bits, x.size))
+    else:
+        assert bytes(q) == bytes(orc.make_qparams(st.mean, res.alpha_star, bits, x.size))
+
+
+def test_gauss_bound_recovers_sigma_of_an_exact_normal_histogram():
+    # histogram built from the normal cdf: its peak density is 1/(sigma sqrt(2 pi)) up to the bin width
+    sigma, n, nbins = 0.8, 10_000_000, 2048
+    edges = np.linspace(-6 * sigma, 6 * sigma, nbins + 1)
+    cdf = scipy.special.ndtr(edges / sigma)
+    peak = float(np.max(np.diff(cdf))) / (edges[1] - edges[0])
+    assert 1.0 / (np.sqrt(2 * np.pi) * peak) == pytest.approx(sigma, rel=1e-4)
+    # and on a real sample the oracle's bound lands near sigma (peak of a noisy histogram is biased upwards)
+    x = (np.random.default_rng(5).standard_normal(400_000) * sigma).astype(np.float32)
+    rc, st = orc.stats(x, nbins=128)
+    res, q, scores = orc.dsaciq_search_variant(x, st, 4, 10, dist=orc.GAUSS)
+    assert res.b_e == pytest.approx(sigma, rel=5e-3)
+    assert res.b_r == pytest.approx(sigma, rel=5e-2) and res.b_r < sigma * 1.001
+
+
+def test_intersecting_with_the_data_range_helps_one_sided_data_and_is_neutral_otherwise():
+    x = si.make_config("C3", n=60_000)          # after a GELU: min about -0.17, long right tail
+    rc, st = orc.stats(x)
+    for bits in (2, 4):
+        r0, _, s0 = orc.dsaciq_search(x, st, bits, 40)
+        r1, _, s1 = orc.dsaciq_search_variant(x, st, bits, 40, clip_to_data=True)
+        assert r1.mse_star < 0.85 * r0.mse_star
+    x = si.make_config("C1", n=60_000)          # symmetric with outliers: every candidate range lies inside the data's
+    rc, st = orc.stats(x)
+    r0, q0, s0 = orc.dsaciq_search(x, st, 4, 40)
+    r1, q1, s1 = orc.dsaciq_search_variant(x, st, 4, 40, clip_to_data=True)
+    assert np.array_equal(s0, s1) and bytes(q0) == bytes(q1)
+
+
+@pytest.mark.parametrize("t,stride", [(100, 10), (100, 7), (100, 1), (37, 5), (10, 10), (10, 30), (1, 3), (255, 16)])
+def test_coarse_to_fine_pick_finds_the_minimum_of_a_unimodal_curve(t, stride):
+    rng = np.random.default_rng(t * 31 + stride)
+    for trial in range(200):
+        m = int(rng.integers(0, t + 1))
+        down = np.sort(rng.random(m))[::-1] + 1.0          # strictly falling to the minimum ...
+        up = np.sort(rng.random(t - m)) + 1.0              # ... and rising after it
+        scores = np.concatenate([down, [0.5], up])
+        j, ev = orc.c2f_pick(scores, stride)
+        assert j == m == int(np.argmin(scores))
+        assert ev.sum() <= -(-t // stride) + 1 + 2 * stride - 1
+
+
+def test_coarse_to_fine_pick_on_arbitrary_curves_is_the_first_minimum_of_what_it_evaluates():
+    rng = np.random.default_rng(11)
+    for trial in range(300):
+        t = int(rng.integers(1, 120))
+        stride = int(rng.integers(1, 25))
+        scores = rng.integers(0, 6, size=t + 1).astype(np.float64)      # many ties
+        j, ev = orc.c2f_pick(scores, stride)
+        coarse = sorted(set(min(i * stride, t) for i in range(t // stride + 2)))
+        assert all(ev[c] for c in coarse)
+        j1 = min(coarse, key=lambda c: (scores[c], c))
+        window = range(max(0, j1 - stride + 1), min(t, j1 + stride - 1) + 1)
+        assert all(ev[c] for c in window) and ev.sum() == len(set(coarse) | set(window))
+        assert j == min(window, key=lambda c: (scores[c], c))
+        assert scores[j] == scores[ev].min()                             # nothing evaluated is better
+
+
+def test_coarse_to_fine_search_equals_pick_on_the_full_sweep():
+    for name, bits, clip in (("C1", 2, False), ("C3", 4, True), ("C2", 8, False), ("C3", 2, False)):
+        x = si.make_config(name, n=20_000)
+        rc, st = orc.stats(x)
+        full_r, full_q, full = orc.dsaciq_search_variant(x, st, bits, 100, clip_to_data=clip)
+        for stride in (10, 4):
+            r, q, sc = orc.dsaciq_search_variant(x, st, bits, 100, clip_to_data=clip, stride=stride)
+            j, ev = orc.c2f_pick(full, stride)
+            assert r.j_star == j
+            assert np.array_equal(sc[ev], full[ev]) and np.isnan(sc[~ev]).all()
+            assert r.mse_aciq == full_r.mse_aciq and r.mse_star == full[j] / x.size
+            if j == full_r.j_star:       # the usual case: the error curve has one valley
+                assert bytes(q) == bytes(full_q) and r.alpha_star == full_r.alpha_star
+        # on these inputs the sweep with stride 10 does find the full sweep's winner
+        assert orc.c2f_pick(full, 10)[0] == full_r.j_star
