@@ -84,14 +84,37 @@ typedef struct {
     float    inv_scale;    /* (2^bits - 1) / (hi - lo); 0 if hi == lo */
 } qp_qparams_t;
 
-/* Directed-search configuration.  The paper sets t_steps = 100 (Sec. 3). */
+/* Directed-search configuration.  The paper sets t_steps = 100 (Sec. 3), models the data as
+ * Laplace, clips symmetrically about mu and sweeps all t_steps + 1 candidates: that is what a
+ * zeroed `dist`, `flags` and `coarse_stride` give (and what qp_default_search_cfg() returns).
+ * The other settings are variations on Eq. 1 beyond the paper, each with its own oracle:
+ *   dist = QP_GAUSS             the Gaussian model of the ACIQ method the paper builds on: scale
+ *                               estimate sigma_E = sqrt(var), alpha = G(q) sigma, search bound
+ *                               sigma_R = 1 / (sqrt(2 pi) max(D_R)) (the sigma whose density peak
+ *                               equals the histogram's);
+ *   QP_SEARCH_CLIP_TO_DATA      every candidate range is intersected with the data's own range,
+ *                               [max(mu - alpha, min), min(mu + alpha, max)], so one-sided data
+ *                               (after a GELU) spends no levels below its minimum;
+ *   QP_SEARCH_COARSE_TO_FINE    two sweeps instead of one: candidates j = 0, s, 2s, ..., t first,
+ *                               then every candidate within s - 1 of the coarse winner; the first
+ *                               minimum of the second sweep wins.  Equal to the full sweep's
+ *                               result whenever the error curve has a single valley, with about
+ *                               t/s + 2s evaluations instead of t + 1.  s = coarse_stride
+ *                               (0 = 10; at most 64).  Scores of candidates that were never
+ *                               evaluated are NaN in QP_WS_SCORES.  Available for fp32 tensors of
+ *                               at most 2^21 elements and bf16 tensors of fewer than 2^20; larger
+ *                               ones are refused with QP_EINVAL (use the full sweep). */
+#define QP_SEARCH_CLIP_TO_DATA 1u
+#define QP_SEARCH_COARSE_TO_FINE 2u
 typedef struct {
     uint32_t t_steps;          /* 1..1023: candidates j = 0..t_steps */
     uint32_t cands_per_round;  /* 1..32: most candidates scored per pass over the tensor (small tensors use
                                   fewer); never changes results.  Default 13: eight even rounds of the 101
                                   candidates, which is what the gfx950 register file likes best */
     uint32_t nbins;            /* kept with the configuration for callers; the search itself does not use it */
-    uint32_t dist;             /* must be QP_LAPLACE (the paper's model) */
+    uint32_t dist;             /* QP_LAPLACE (the paper's model) or QP_GAUSS */
+    uint32_t flags;            /* QP_SEARCH_* bits, 0 = the paper's method */
+    uint32_t coarse_stride;    /* see QP_SEARCH_COARSE_TO_FINE */
 } qp_search_cfg_t;
 
 typedef struct {
@@ -126,7 +149,7 @@ size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg);
 /* Byte offset of a region inside the workspace; (size_t)-1 for an unknown region. */
 size_t qp_ws_offset(qp_ws_region region);
 
-/* Fills cfg with the defaults {100, 13, 2048, QP_LAPLACE}. */
+/* Fills cfg with the defaults {100, 13, 2048, QP_LAPLACE, 0, 0}: the paper's method. */
 void qp_default_search_cfg(qp_search_cfg_t *cfg);
 
 /* ---- step 1: statistics (Sec. 3: mu and b of L(mu, b); b_E; histogram D_R; b_R) ----
@@ -153,6 +176,12 @@ double qp_aciq_constant(uint32_t bits, qp_dist dist);
  * Naive PTQ (Sec. 3) is center = (min+max)/2, alpha = (max-min)/2. */
 qp_status qp_make_qparams(double center, double alpha, uint32_t bits, uint64_t n, qp_qparams_t *out);
 
+/* The same grid for the range intersected with the data's own range (rounded to fp32):
+ * [max(center - alpha, data_min), min(center + alpha, data_max)]; scale 0 if that is empty.
+ * This is the winner's grid of a search run with QP_SEARCH_CLIP_TO_DATA.  Host only, pure. */
+qp_status qp_make_qparams_clipped(double center, double alpha, double data_min, double data_max, uint32_t bits,
+                                  uint64_t n, qp_qparams_t *out);
+
 /* ---- step 2b: DS-ACIQ directed search (Sec. 3, Eq. 1) -------------------------
  * Candidates b_j = b_E + j (b_R - b_E) / t, j = 0..t, with b_E = stats->mad and
  * b_R = stats->b_r, whichever way that points.  Each is scored by the squared
@@ -164,7 +193,10 @@ qp_status qp_make_qparams(double center, double alpha, uint32_t bits, uint64_t n
  * The tensor is read once per round of cfg->cands_per_round candidates.
  * qp_dsaciq_search returns the result and the winner's grid to the host (either may be
  * NULL); the async form takes the statistics that qp_stats_async left in the same
- * workspace and leaves QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES there. */
+ * workspace and leaves QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES there.
+ * With cfg->dist = QP_GAUSS the grid runs from sqrt(stats->var) to
+ * 1 / (sqrt(2 pi) stats->peak_density) and alpha_j = G(q) sigma_j (b_e, b_r, b_star of the
+ * result then hold sigmas); cfg->flags are described at qp_search_cfg_t. */
 qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats,
                            uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
                            void *stream, qp_search_result_t *res_host, qp_qparams_t *qparams_out_host);
@@ -178,7 +210,8 @@ qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, 
  * of candidate j is sum over bins of (D_R,i - exp(-|c_i - mu| / b_j) / (2 b_j))^2 with c_i the
  * bin centre and D_R,i = count_i / (N binwidth); mse_aciq / mse_star are means over the bins.
  * Works on the statistics record and histogram that qp_stats / qp_stats_async left in ws_dev
- * (no pass over the tensor) and overwrites QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES. */
+ * (no pass over the tensor) and overwrites QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES.
+ * Only the paper's form: cfg->dist must be QP_LAPLACE and cfg->flags 0 (else QP_EINVAL). */
 qp_status qp_dsaciq_hist_search(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
                                 void *stream, qp_search_result_t *res_host, qp_qparams_t *qparams_out_host);
 qp_status qp_dsaciq_hist_search_async(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,

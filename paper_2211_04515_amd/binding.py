@@ -13,10 +13,11 @@ import torch  # noqa: F401  (must precede CDLL: one HIP runtime per process)
 
 __all__ = [
     "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS",
+    "QP_SEARCH_CLIP_TO_DATA", "QP_SEARCH_COARSE_TO_FINE",
     "QP_WS_STATS", "QP_WS_RESULT", "QP_WS_QPARAMS", "QP_WS_HIST", "QP_WS_CANDS", "QP_WS_SCORES",
     "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "QuantPipeError", "BITS",
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
-    "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_dsaciq_search",
+    "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
     "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
     "qp_compress_async", "qp_next_bits", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
 ]
@@ -24,6 +25,7 @@ __all__ = [
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
 QP_F32, QP_BF16 = 0, 1
 QP_LAPLACE, QP_GAUSS = 0, 1
+QP_SEARCH_CLIP_TO_DATA, QP_SEARCH_COARSE_TO_FINE = 1, 2
 QP_WS_STATS, QP_WS_RESULT, QP_WS_QPARAMS, QP_WS_HIST, QP_WS_CANDS, QP_WS_SCORES = range(6)
 BITS = (2, 3, 4, 6, 8, 16)
 
@@ -44,7 +46,7 @@ class qp_qparams_t(C.Structure):
 
 class qp_search_cfg_t(C.Structure):
     _fields_ = [("t_steps", C.c_uint32), ("cands_per_round", C.c_uint32), ("nbins", C.c_uint32),
-                ("dist", C.c_uint32)]
+                ("dist", C.c_uint32), ("flags", C.c_uint32), ("coarse_stride", C.c_uint32)]
 
 
 class qp_search_result_t(C.Structure):
@@ -81,6 +83,8 @@ def lib():
             "qp_aciq_alpha": (i32, [C.POINTER(qp_stats_t), u32, i32, C.POINTER(C.c_double)]),
             "qp_aciq_constant": (C.c_double, [u32, i32]),
             "qp_make_qparams": (i32, [C.c_double, C.c_double, u32, u64, C.POINTER(qp_qparams_t)]),
+            "qp_make_qparams_clipped": (i32, [C.c_double, C.c_double, C.c_double, C.c_double, u32, u64,
+                                              C.POINTER(qp_qparams_t)]),
             "qp_dsaciq_search": (i32, [vp, u64, i32, C.POINTER(qp_stats_t), u32, C.POINTER(qp_search_cfg_t), vp, sz,
                                        vp, C.POINTER(qp_search_result_t), C.POINTER(qp_qparams_t)]),
             "qp_dsaciq_search_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp]),
@@ -104,7 +108,7 @@ def lib():
 
 
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
-           "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_dsaciq_search",
+           "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
            "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
            "qp_unpack_dequant_dev", "qp_compress_async", "qp_next_bits", "qp_strerror")
 
@@ -211,6 +215,13 @@ def qp_aciq_constant(bits: int, dist: int = QP_LAPLACE) -> float:
 def qp_make_qparams(center: float, alpha: float, bits: int, n: int) -> qp_qparams_t:
     q = qp_qparams_t()
     _check(lib().qp_make_qparams(float(center), float(alpha), int(bits), int(n), C.byref(q)), "qp_make_qparams")
+    return q
+
+
+def qp_make_qparams_clipped(center: float, alpha: float, data_min: float, data_max: float, bits: int, n: int) -> qp_qparams_t:
+    q = qp_qparams_t()
+    _check(lib().qp_make_qparams_clipped(float(center), float(alpha), float(data_min), float(data_max), int(bits), int(n),
+                                         C.byref(q)), "qp_make_qparams_clipped")
     return q
 
 

@@ -65,8 +65,25 @@ qp_status check_cfg(const qp_search_cfg_t *cfg)
     if (!cfg) return QP_OK;
     if (cfg->t_steps < 1 || cfg->t_steps > kMaxT) return QP_EINVAL;
     if (cfg->cands_per_round < 1 || cfg->cands_per_round > kMaxCandsPerRound) return QP_EINVAL;
-    if (cfg->dist != QP_LAPLACE) return QP_EINVAL;
+    if (cfg->dist != QP_LAPLACE && cfg->dist != QP_GAUSS) return QP_EINVAL;
+    if (cfg->flags & ~(QP_SEARCH_CLIP_TO_DATA | QP_SEARCH_COARSE_TO_FINE)) return QP_EINVAL;
+    if (cfg->coarse_stride > 64u) return QP_EINVAL;
     return QP_OK;
+}
+
+// The host's decisions about one search (cfg already checked).
+SearchPlan make_plan(uint32_t bits, const qp_search_cfg_t *cfg)
+{
+    SearchPlan p;
+    p.bits = bits;
+    p.t_steps = cfg ? cfg->t_steps : 100u;
+    p.cpr = cfg ? cfg->cands_per_round : 13u;
+    p.dist = cfg ? cfg->dist : (uint32_t)QP_LAPLACE;
+    p.C = p.dist == QP_GAUSS ? gauss_constant(bits) : laplace_constant(bits);
+    p.clip = (cfg && (cfg->flags & QP_SEARCH_CLIP_TO_DATA)) ? 1u : 0u;
+    p.stride = 1u;
+    if (cfg && (cfg->flags & QP_SEARCH_COARSE_TO_FINE)) p.stride = cfg->coarse_stride ? cfg->coarse_stride : 10u;
+    return p;
 }
 
 qp_status hip_status(hipError_t e) { return e == hipSuccess ? QP_OK : QP_EHIP; }
@@ -88,6 +105,8 @@ void qp_default_search_cfg(qp_search_cfg_t *cfg)
     cfg->cands_per_round = 13;
     cfg->nbins = 2048;
     cfg->dist = QP_LAPLACE;
+    cfg->flags = 0;
+    cfg->coarse_stride = 0;
 }
 
 size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg)
@@ -95,10 +114,12 @@ size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg)
     if (n == 0 || n > kMaxN) return 0;
     if (check_cfg(cfg) != QP_OK) return 0;
     const uint32_t t = cfg ? cfg->t_steps : 100u;
-    // partial sums: one column per block of whichever search kernel the size selects
+    // partial sums: one column per block of whichever search kernel the size selects, one row per
+    // candidate of the longest sweep (the fine sweep of a coarse-to-fine search has up to 127)
     uint32_t cols = search_blocks(n);
-    if (tile_search_eligible(n, t) && tile_search_blocks(n) > cols) cols = tile_search_blocks(n);
-    return kOffSearchPart + (size_t)cols * (t + 1u) * sizeof(double);
+    if (tile_search_blocks(n) > cols) cols = tile_search_blocks(n);
+    const uint32_t rows = t + 1u > 128u ? t + 1u : 128u;
+    return kOffSearchPart + (size_t)cols * rows * sizeof(double);
 }
 
 size_t qp_ws_offset(qp_ws_region region)
@@ -165,6 +186,17 @@ qp_status qp_make_qparams(double center, double alpha, uint32_t bits, uint64_t n
     return QP_OK;
 }
 
+qp_status qp_make_qparams_clipped(double center, double alpha, double data_min, double data_max, uint32_t bits,
+                                  uint64_t n, qp_qparams_t *out)
+{
+    if (!out || !bits_ok(bits)) return QP_EINVAL;
+    out->bits = bits;
+    out->reserved = 0;
+    out->n = n;
+    make_grid(center, alpha, bits, out->lo, out->hi, out->scale, out->inv_scale, true, (float)data_min, (float)data_max);
+    return QP_OK;
+}
+
 static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats, uint32_t bits,
                                const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream,
                                uint32_t finalize_nbins = 0)
@@ -173,10 +205,9 @@ static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, co
     if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
     const qp_status w = check_ws(n, cfg, ws_dev, ws_bytes);
     if (w != QP_OK) return w;
-    const uint32_t t = cfg ? cfg->t_steps : 100u;
-    const uint32_t cpr = cfg ? cfg->cands_per_round : 13u;
-    return hip_status(launch_search(x_dev, n, dtype, bits, t, cpr, laplace_constant(bits), stats, finalize_nbins,
-                                    ws_dev, static_cast<hipStream_t>(stream)));
+    const SearchPlan plan = make_plan(bits, cfg);
+    if (plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;   // see quantpipe.h
+    return hip_status(launch_search(x_dev, n, dtype, plan, stats, finalize_nbins, ws_dev, static_cast<hipStream_t>(stream)));
 }
 
 qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
@@ -208,6 +239,7 @@ qp_status qp_dsaciq_hist_search_async(uint32_t bits, const qp_search_cfg_t *cfg,
                                       void *stream)
 {
     if (!bits_ok(bits) || check_cfg(cfg) != QP_OK) return QP_EINVAL;
+    if (cfg && (cfg->dist != QP_LAPLACE || cfg->flags != 0u)) return QP_EINVAL;   // only the paper's form
     if (!ws_dev || !aligned16(ws_dev)) return QP_EINVAL;
     if (ws_bytes < kOffSearchPart) return QP_ENOSPC;   // only the fixed-size head of the workspace is used
     const uint32_t t = cfg ? cfg->t_steps : 100u;
@@ -290,6 +322,10 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
     qp_status st = check_ws(n, cfg, ws_dev, ws_bytes);
     if (st != QP_OK) return st;
+    {   // refuse what the search would refuse before anything is launched
+        const SearchPlan plan = make_plan(bits, cfg);
+        if (plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;
+    }
     // the two statistics passes leave partials; the search finalizes them itself
     st = hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), false));
     if (st != QP_OK) return st;

@@ -40,16 +40,36 @@ struct Cand {
 };
 static_assert(sizeof(Cand) == 16, "Cand layout");
 
+// How a search kernel's candidate list maps to grid indices j (Eq. 1's b_j = b_E + j step).
+enum ListMode : uint32_t {
+    kListFull = 0,     // i -> j = i, i = 0..t: the paper's sweep
+    kListCoarse = 1,   // i -> j = min(i * stride, t)
+    kListFine = 2      // i -> j = clamp(j1 - (stride - 1) + i, 0, t), i = 0..2 stride - 2, j1 the coarse winner
+};
+__device__ __host__ inline uint32_t list_index(uint32_t mode, uint32_t stride, uint32_t j1, uint32_t t_steps, uint32_t i)
+{
+    if (mode == kListFull) return i;
+    if (mode == kListCoarse) {
+        const uint64_t j = (uint64_t)i * stride;
+        return j > t_steps ? t_steps : (uint32_t)j;
+    }
+    const int64_t j = (int64_t)j1 - (int64_t)(stride - 1u) + (int64_t)i;
+    return j < 0 ? 0u : (j > (int64_t)t_steps ? t_steps : (uint32_t)j);
+}
+
 // Device-resident control block.
 struct Ctl {
     uint32_t reserved0;
     uint32_t ticket_search;   // rounds (or candidates) of the search that have finished
     uint32_t short_seq;       // 1: the search may drop the clamp of the rounded level
-    uint32_t pad1;
+    uint32_t clip;            // 1: candidate ranges are intersected with [clip_lo, clip_hi]
     double b_e, b_r, step, F; // search grid: b_j = b_e + j*step, alpha_j = F*b_j
     double mean;
     uint32_t bits, t_steps;
     uint64_t n;
+    uint32_t list_mode, list_stride, list_j1, pad2;
+    float clip_lo, clip_hi;   // the data's range
+    double score0;            // score of j = 0 (plain ACIQ), kept from the coarse sweep for the fine one
 };
 
 // Workspace layout (byte offsets).  Fixed-size regions first, the search partials last.
@@ -64,7 +84,8 @@ constexpr size_t kOffRoundTickets = kOffScores + (kMaxT + 1) * 8; // uint32_t[kM
 constexpr size_t kOffPart1 = kOffRoundTickets + (kMaxT + 1) * 4;  // Part1[kMaxStat1Blocks]
 constexpr size_t kOffPart2 = kOffPart1 + kMaxStat1Blocks * sizeof(Part1);  // Part2[kMaxStat2Blocks]
 constexpr size_t kOffValueCounts = kOffPart2 + kMaxStat2Blocks * sizeof(Part2);  // uint32_t[65536]: bf16 value table
-constexpr size_t kOffSearchPart = kOffValueCounts + 65536 * 4;  // double[t + 1][blocks]
+constexpr size_t kOffListScores = kOffValueCounts + 65536 * 4;   // double[kMaxT + 1]: scores in list order (coarse-to-fine)
+constexpr size_t kOffSearchPart = kOffListScores + (kMaxT + 1) * 8;  // double[t + 1][blocks]
 static_assert(sizeof(qp_stats_t) <= 128 && sizeof(qp_search_result_t) <= 64 && sizeof(qp_qparams_t) == 32 &&
               sizeof(Ctl) <= 256, "fixed workspace regions");
 static_assert(kOffSearchPart % 16 == 0, "alignment");
@@ -210,7 +231,12 @@ __device__ __forceinline__ void st_dev(double *p, double v)
     st_dev(reinterpret_cast<uint64_t *>(p), (uint64_t)__double_as_longlong(v));
 }
 // all of this lane's outstanding memory operations (stores included) have been acknowledged
-__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wait_stores()
+{
+#if defined(__AMDGCN__)   // (the host pass of the compiler only parses this function)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+}
 
 __device__ __forceinline__ void st_dev(Part1 *dst, const Part1 &p)
 {
@@ -435,11 +461,62 @@ __device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uin
     __syncthreads();   // the record is visible to the whole block from here on
 }
 
+// The grid a clipping threshold induces; same statement as qp_make_qparams on the host.  With
+// `clip` the range is first intersected with [mn, mx] (the data's range) and an empty range gives
+// scale 0, as in qp_make_qparams_clipped.
+__device__ __host__ inline void make_grid(double center, double alpha, uint32_t bits, float &lo, float &hi,
+                                          float &scale, float &inv_scale, bool clip = false, float mn = 0.0f,
+                                          float mx = 0.0f)
+{
+    const float a32 = (float)alpha;
+    const float c32 = (float)center;
+    const double L = (double)((1u << bits) - 1u);
+    lo = (float)((double)c32 - (double)a32);
+    hi = (float)((double)c32 + (double)a32);
+    bool empty = (hi == lo);
+    if (clip) {
+        if (lo < mn) lo = mn;
+        if (hi > mx) hi = mx;
+        empty = !(hi > lo);
+    }
+    if (empty) {
+        scale = 0.0f;
+        inv_scale = 0.0f;
+    } else {
+        const double range = (double)hi - (double)lo;
+        scale = (float)(range / L);
+        inv_scale = (float)(L / range);
+    }
+}
+
+// What the host decides about one search: the model, the constant of its threshold, the sweep.
+struct SearchPlan {
+    uint32_t bits, t_steps, cpr;
+    double C;            // F(q) (Laplace) or G(q) (Gaussian): alpha = C * scale
+    uint32_t dist;       // QP_LAPLACE / QP_GAUSS
+    uint32_t clip;       // intersect candidate ranges with the data's range
+    uint32_t stride;     // 1: all t + 1 candidates; > 1: coarse sweep with this stride, then a fine one
+};
+
+// The two ends of the scale grid under a model: the moment estimate and the bound given by the
+// histogram's peak.  Laplace (Sec. 3): b_E = MAD, b_R = 1 / (2 max D_R).  Gaussian: sigma_E =
+// sqrt(var), sigma_R = 1 / (sqrt(2 pi) max D_R); 0 when the data has one distinct value.
+__device__ __host__ inline void scale_ends(const qp_stats_t &st, uint32_t dist, double &s_e, double &s_r)
+{
+    if (dist == QP_GAUSS) {
+        s_e = sqrt(st.var);
+        s_r = (st.peak_density == 0.0) ? 0.0 : 1.0 / (2.5066282746310002 /* sqrt(2 pi) */ * st.peak_density);
+    } else {
+        s_e = st.mad;
+        s_r = st.b_r;
+    }
+}
+
 // First minimum of scores[0 .. ncand) taken by one full wave: a candidate replaces the incumbent
 // only if its score is strictly lower, so ties keep the smaller index (b_E is kept unless
-// something is strictly better) and a NaN score never wins; a NaN incumbent (j = 0) is never
-// beaten.  Lanes scan j = lane, lane + 64, ... in ascending order, then a shuffle tree.  Every
-// lane returns the winner's index.
+// something is strictly better) and a NaN score never wins.  Lanes scan j = lane, lane + 64, ...
+// in ascending order, then a shuffle tree.  Every lane returns the winner's index.  (The caller
+// applies the rule that a NaN score of plain ACIQ, j = 0, is never beaten.)
 __device__ __forceinline__ uint32_t first_min_wave(const double *scores, uint32_t ncand, uint32_t lane)
 {
     double bs = INFINITY;
@@ -460,9 +537,118 @@ __device__ __forceinline__ uint32_t first_min_wave(const double *scores, uint32_
             bj = oj;
         }
     }
-    const double s0 = scores[0];
-    if (!(s0 == s0)) bj = 0u;
     return bj;
+}
+
+// What the winner of a candidate list means for the search, written by one lane: the result
+// record, the winner's grid and (for the fine sweep that may follow) the score of j = 0.
+// `scores` holds the list's scores; in a coarse-to-fine search they are also scattered to
+// scores_by_j (which the set-up filled with NaN).
+__device__ inline void write_search_result(Ctl *ctl, const double *scores, uint32_t ncand, uint32_t bi, uint64_t n_total,
+                                           double *scores_by_j, qp_search_result_t *res, qp_qparams_t *best)
+{
+    const uint32_t mode = ctl->list_mode, stride = ctl->list_stride, j1 = ctl->list_j1, t = ctl->t_steps;
+    // plain ACIQ's score: entry 0 of the full and of the coarse list; the fine list may not hold j = 0
+    const double s0 = (mode == kListFine) ? ctl->score0 : scores[0];
+    uint32_t j = list_index(mode, stride, j1, t, bi);
+    double sbest = scores[bi];
+    if (!(s0 == s0)) {   // a NaN incumbent is never beaten
+        j = 0u;
+        sbest = s0;
+    }
+    if (mode != kListFull)
+        for (uint32_t i = 0; i < ncand; ++i) scores_by_j[list_index(mode, stride, j1, t, i)] = scores[i];
+    qp_search_result_t r;
+    r.b_e = ctl->b_e;
+    r.b_r = ctl->b_r;
+    r.b_star = ctl->b_e + (double)j * ctl->step;
+    r.alpha_star = ctl->F * r.b_star;
+    r.mse_aciq = s0 / (double)n_total;
+    r.mse_star = sbest / (double)n_total;
+    r.j_star = j;
+    r.t_steps = t;
+    *res = r;
+    qp_qparams_t q;
+    q.bits = ctl->bits;
+    q.reserved = 0u;
+    q.n = n_total;
+    make_grid(ctl->mean, r.alpha_star, ctl->bits, q.lo, q.hi, q.scale, q.inv_scale, ctl->clip != 0u, ctl->clip_lo,
+              ctl->clip_hi);
+    *best = q;
+    ctl->score0 = s0;
+    ctl->ticket_search = 0u;
+}
+
+// What a kernel needs to build one sweep's candidate table.
+struct ModelArgs {
+    double mean_h, s_e_h, s_r_h;    // statistics from the host (from_ws == 0): mean and the two scale ends
+    float clip_lo_h, clip_hi_h;     // ... and the data's range
+    int from_ws;                    // 1: take them from the statistics record in the workspace
+    uint32_t dist, clip;
+    uint32_t list_mode, list_stride, count;   // the sweep: count candidates, list entry i -> grid index j
+    uint32_t bits, t_steps;
+    double C;
+};
+
+// Run by a whole block: candidate i of the list gets the grid of scale s_j = s_E + j (s_R - s_E)/t,
+// alpha_j = C s_j, centred on the mean (Eq. 1).  A bound or estimate that is zero, negative or not
+// finite collapses the grid onto s_E.  Writes the table to cands_a (and cands_b if given), the
+// control record if given, and before a coarse sweep fills scores_by_j with NaN ("not evaluated").
+//
+// Returns (to every lane) whether the search may use its short per-element sequence.  The full
+// sequence clamps twice: x to [lo, hi] before the subtraction and the rounded level to [0, L]
+// after it.  With x already clamped, d = x - lo lies in [0, fl(hi - lo)], t = d*inv is monotone
+// in d (inv >= 0) and rounding is monotone, so the level lies in [0, rint(fl(fl(hi - lo)*inv))]:
+// if that upper end, evaluated here in the kernels' own fp32 arithmetic, is at most L for every
+// candidate (it is whenever the range is a normal number), the second clamp can never act.
+__device__ inline int setup_candidates(const ModelArgs &m, const qp_stats_t *st, uint32_t j1, uint64_t n, Cand *cands_a,
+                                       Cand *cands_b, Ctl *ctl, double *scores_by_j)
+{
+    double mean = m.mean_h, s_e = m.s_e_h, s_r = m.s_r_h;
+    float clo = m.clip_lo_h, chi = m.clip_hi_h;
+    if (st) {
+        mean = st->mean;
+        scale_ends(*st, m.dist, s_e, s_r);
+        clo = (float)st->min;
+        chi = (float)st->max;
+    }
+    double step = (s_r - s_e) / (double)m.t_steps;
+    const bool ok = (s_e > 0.0) && (s_r > 0.0) && isfinite(s_r) && isfinite(s_e) && isfinite(step);
+    if (!ok) step = 0.0;
+    const float Lf = (float)((1u << m.bits) - 1u);
+    int safe = 1;
+    for (uint32_t i = threadIdx.x; i < m.count; i += blockDim.x) {
+        const uint32_t j = list_index(m.list_mode, m.list_stride, j1, m.t_steps, i);
+        const double s_j = s_e + (double)j * step;
+        Cand c;
+        make_grid(mean, m.C * s_j, m.bits, c.lo, c.hi, c.scale, c.inv_scale, m.clip != 0u, clo, chi);
+        cands_a[i] = c;
+        if (cands_b) cands_b[i] = c;
+        const float top = rintf((c.hi - c.lo) * c.inv_scale);
+        if (!(isfinite(c.lo) && isfinite(c.hi) && top >= 0.0f && top <= Lf)) safe = 0;
+    }
+    if (scores_by_j && m.list_mode == kListCoarse)
+        for (uint32_t j = threadIdx.x; j <= m.t_steps; j += blockDim.x) scores_by_j[j] = __longlong_as_double(0x7ff8000000000000ll);
+    safe = __syncthreads_and(safe);
+    if (ctl && threadIdx.x == 0) {
+        ctl->ticket_search = 0u;
+        ctl->short_seq = (uint32_t)safe;
+        ctl->clip = m.clip;
+        ctl->b_e = s_e;
+        ctl->b_r = s_r;
+        ctl->step = step;
+        ctl->F = m.C;
+        ctl->mean = mean;
+        ctl->bits = m.bits;
+        ctl->t_steps = m.t_steps;
+        ctl->n = n;
+        ctl->list_mode = m.list_mode;
+        ctl->list_stride = m.list_stride;
+        ctl->list_j1 = j1;
+        ctl->clip_lo = clo;
+        ctl->clip_hi = chi;
+    }
+    return safe;
 }
 
 // What a search kernel needs to turn the partials of the statistics passes into the record itself
@@ -480,25 +666,6 @@ struct FinalizeArgs {
 #endif
 constexpr uint64_t kTileSearchMaxN = QP_TILE_SEARCH_MAX_N;
 
-// The grid a clipping threshold induces; same statement as qp_make_qparams on the host.
-__device__ __host__ inline void make_grid(double center, double alpha, uint32_t bits, float &lo, float &hi,
-                                          float &scale, float &inv_scale)
-{
-    const float a32 = (float)alpha;
-    const float c32 = (float)center;
-    const double L = (double)((1u << bits) - 1u);
-    lo = (float)((double)c32 - (double)a32);
-    hi = (float)((double)c32 + (double)a32);
-    if (hi == lo) {
-        scale = 0.0f;
-        inv_scale = 0.0f;
-    } else {
-        const double range = (double)hi - (double)lo;
-        scale = (float)(range / L);
-        inv_scale = (float)(L / range);
-    }
-}
-
 inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 
 // Kernel launchers (one per translation unit); all return hipError_t from hipGetLastError().
@@ -507,11 +674,13 @@ inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b 
 hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s, bool finalize);
 void stats_grid(uint64_t n, int dtype, uint32_t &nb1, uint32_t &nb2);
 // Set-up + search.  stats_host_or_null: statistics from the host, else they are taken from the
-// workspace; finalize_nbins != 0: the set-up kernel first finalizes the statistics that
+// workspace; finalize_nbins != 0: the search first finalizes the statistics that
 // launch_stats(..., finalize = false) left as partials (histogram of finalize_nbins bins).
-hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
-                         double F, const qp_stats_t *stats_host_or_null, uint32_t finalize_nbins, void *ws,
-                         hipStream_t s);
+hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *stats_host_or_null,
+                         uint32_t finalize_nbins, void *ws, hipStream_t s);
+bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan);
+// The host's part of ModelArgs for one sweep of a plan.
+ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *stats_host_or_null, uint32_t list_mode, uint32_t count);
 hipError_t launch_stats_finalize(uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s);
 uint32_t search_blocks(uint64_t n);
 hipError_t launch_hist_search(uint32_t bits, uint32_t t_steps, double F, void *ws, hipStream_t s);
@@ -519,9 +688,9 @@ hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits
                              const qp_qparams_t *dev_qp, void *packed, hipStream_t s);
 // The search with one candidate per lane over LDS-staged tiles, for tensors of at most
 // kTileSearchMaxN elements and at most 256 candidates (same arguments as launch_search).
-bool tile_search_eligible(uint64_t n, uint32_t t_steps);
+bool tile_search_eligible(uint64_t n, const SearchPlan &plan);
 uint32_t tile_search_blocks(uint64_t n);
-hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, double F,
+hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan,
                               const qp_stats_t *stats_host_or_null, uint32_t finalize_nbins, void *ws, hipStream_t s);
 hipError_t launch_unpack_dequant(const void *packed, uint32_t bits, const qp_qparams_t *host_qp,
                                  const qp_qparams_t *dev_qp, float *y, uint64_t n, hipStream_t s);

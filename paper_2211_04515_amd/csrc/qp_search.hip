@@ -36,62 +36,23 @@ constexpr uint64_t kValueTableMinN = 1ull << 20;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
-// One block: fills the candidate table and the control record.
-//
-// It also decides whether the search may use its short per-element sequence.  The full
-// sequence clamps twice: x to [lo, hi] before the subtraction and the rounded level to
-// [0, L] after it.  With x already clamped, d = x - lo lies in [0, fl(hi - lo)], t = d*inv is
-// monotone in d (inv >= 0) and rounding is monotone, so the level lies in
-// [0, rint(fl(fl(hi - lo)*inv))]: if that upper end, evaluated here in the kernel's own fp32
-// arithmetic, is at most L for every candidate (it is whenever the range is a normal number),
-// the second clamp can never act and is dropped.  Otherwise the full sequence is used.
-//
+// One block: fills the candidate table and the control record for one sweep (setup_candidates).
 // When the statistics passes have only left their partials (the fused sender path), this block
-// first turns them into the qp_stats_t record, which saves a launch.
-__global__ __launch_bounds__(kFinThreads) void k_search_setup(qp_stats_t *__restrict__ stats_dev, double mean_h,
-                                                              double b_e_h, double b_r_h, int from_ws, uint32_t bits,
-                                                              uint32_t t_steps, double F, uint64_t n,
+// first turns them into the qp_stats_t record, which saves a launch.  Before the fine sweep of a
+// coarse-to-fine search it reads the coarse winner from the result record (prev).
+__global__ __launch_bounds__(kFinThreads) void k_search_setup(ModelArgs m, qp_stats_t *__restrict__ stats_dev, uint64_t n,
                                                               Cand *__restrict__ cands, Ctl *__restrict__ ctl,
                                                               uint32_t *__restrict__ round_tickets, FinalizeArgs fin,
-                                                              uint32_t *__restrict__ value_counts)
+                                                              uint32_t *__restrict__ value_counts,
+                                                              const qp_search_result_t *__restrict__ prev,
+                                                              double *__restrict__ scores_by_j)
 {
     for (uint32_t j = threadIdx.x; j <= kMaxT; j += blockDim.x) round_tickets[j] = 0u;
     if (value_counts)   // the bf16 value table is accumulated with atomics by the next kernel
         for (uint32_t j = threadIdx.x; j < kNumValues16; j += blockDim.x) value_counts[j] = 0u;
     if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
-    double mean = mean_h, b_e = b_e_h, b_r = b_r_h;
-    if (from_ws) {
-        mean = stats_dev->mean;
-        b_e = stats_dev->mad;
-        b_r = stats_dev->b_r;
-    }
-    double step = (b_r - b_e) / (double)t_steps;
-    const bool ok = (b_e > 0.0) && (b_r > 0.0) && isfinite(b_r) && isfinite(b_e) && isfinite(step);
-    if (!ok) step = 0.0;   // the grid collapses onto b_E
-    const float Lf = (float)((1u << bits) - 1u);
-    int safe = 1;
-    for (uint32_t j = threadIdx.x; j <= t_steps; j += blockDim.x) {
-        const double b_j = b_e + (double)j * step;
-        const double alpha = F * b_j;
-        Cand c;
-        make_grid(mean, alpha, bits, c.lo, c.hi, c.scale, c.inv_scale);
-        cands[j] = c;
-        const float top = rintf((c.hi - c.lo) * c.inv_scale);
-        if (!(isfinite(c.lo) && isfinite(c.hi) && top >= 0.0f && top <= Lf)) safe = 0;
-    }
-    safe = __syncthreads_and(safe);
-    if (threadIdx.x == 0) {
-        ctl->ticket_search = 0u;
-        ctl->short_seq = (uint32_t)safe;
-        ctl->b_e = b_e;
-        ctl->b_r = b_r;
-        ctl->step = step;
-        ctl->F = F;
-        ctl->mean = mean;
-        ctl->bits = bits;
-        ctl->t_steps = t_steps;
-        ctl->n = n;
-    }
+    const uint32_t j1 = (m.list_mode == kListFine) ? prev->j_star : 0u;
+    setup_candidates(m, m.from_ws ? stats_dev : nullptr, j1, n, cands, nullptr, ctl, scores_by_j);
 }
 
 // The scoring pass of one block: lanes stride over batches of kSrElems elements; for each
@@ -250,7 +211,8 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
                                                            double *__restrict__ scores, Ctl *__restrict__ ctl,
                                                            uint32_t *__restrict__ round_tickets,
                                                            qp_search_result_t *__restrict__ res,
-                                                           qp_qparams_t *__restrict__ best, uint64_t n_total)
+                                                           qp_qparams_t *__restrict__ best, uint64_t n_total,
+                                                           double *__restrict__ scores_by_j)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t c0 = blockIdx.y * cpr;
@@ -322,28 +284,8 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     if (!sh_flag || wave != 0) return;
     QP_TICKET_ACQUIRE();
 
-    const uint32_t bj = first_min_wave(scores, ncand, lane);
-    if (lane == 0) {
-        const double s0 = scores[0];
-        const double sbest = scores[bj];
-        qp_search_result_t r;
-        r.b_e = ctl->b_e;
-        r.b_r = ctl->b_r;
-        r.b_star = ctl->b_e + (double)bj * ctl->step;
-        r.alpha_star = ctl->F * r.b_star;
-        r.mse_aciq = s0 / (double)n_total;
-        r.mse_star = sbest / (double)n_total;
-        r.j_star = bj;
-        r.t_steps = ncand - 1u;
-        *res = r;
-        qp_qparams_t q;
-        q.bits = ctl->bits;
-        q.reserved = 0u;
-        q.n = n_total;
-        make_grid(ctl->mean, r.alpha_star, ctl->bits, q.lo, q.hi, q.scale, q.inv_scale);
-        *best = q;
-        ctl->ticket_search = 0u;
-    }
+    const uint32_t bi = first_min_wave(scores, ncand, lane);
+    if (lane == 0) write_search_result(ctl, scores, ncand, bi, n_total, scores_by_j, res, best);
 }
 
 // ---- the other reading of Eq. 1: fit the Laplace pdf to the histogram -----------------
@@ -393,9 +335,10 @@ __global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__
     if (!sh_flag || wave != 0) return;
     QP_TICKET_ACQUIRE();
 
-    const uint32_t bj = first_min_wave(scores, ncand, lane);
+    uint32_t bj = first_min_wave(scores, ncand, lane);
     if (lane == 0) {
         const double s0 = scores[0];
+        if (!(s0 == s0)) bj = 0u;   // a NaN incumbent is never beaten
         qp_search_result_t r;
         r.b_e = b_e;
         r.b_r = b_r;
@@ -469,7 +412,8 @@ struct SearchArgs {
     uint32_t *round_tickets;
     qp_search_result_t *res;
     qp_qparams_t *best;
-    uint64_t n_total;   // elements of the tensor (differs from n only on the value-table path)
+    uint64_t n_total;      // elements of the tensor (differs from n only on the value-table path)
+    double *scores_by_j;   // where a coarse-to-fine sweep scatters its scores
 };
 
 // Picks the round structure and the grid for one kernel variant and launches it.
@@ -491,48 +435,71 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
     if (gx > cols) gx = cols;
     if (gx < 1) gx = 1;
     hipLaunchKernelGGL((k_search_mse<DT, CMAX>), dim3(gx, rounds), dim3(kSrThreads), 0, s, a.x, a.n, a.cands, a.ncand,
-                       cpr_eff, a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.n_total);
+                       cpr_eff, a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.n_total,
+                       a.scores_by_j);
     return hipGetLastError();
 }
 
-hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, uint32_t cpr,
-                         double F, const qp_stats_t *st, uint32_t finalize_nbins, void *ws, hipStream_t s)
+ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *st, uint32_t list_mode, uint32_t count)
 {
-    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
-    // them once (one pass over the tensor) and run the candidates over the value table.
-    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
-    // other small and medium tensors: one candidate per lane over LDS tiles
-    if (!by_values && tile_search_eligible(n, t_steps))
-        return launch_tile_search(x, n, dtype, bits, t_steps, F, st, finalize_nbins, ws, s);
+    ModelArgs m{};
+    m.from_ws = st ? 0 : 1;
+    if (st) {
+        m.mean_h = st->mean;
+        scale_ends(*st, plan.dist, m.s_e_h, m.s_r_h);
+        m.clip_lo_h = (float)st->min;
+        m.clip_hi_h = (float)st->max;
+    }
+    m.dist = plan.dist;
+    m.clip = plan.clip;
+    m.list_mode = list_mode;
+    m.list_stride = plan.stride;
+    m.count = count;
+    m.bits = plan.bits;
+    m.t_steps = plan.t_steps;
+    m.C = plan.C;
+    return m;
+}
+
+// One sweep of the streaming search (or of the value-table search): set-up kernel, then the search kernel.
+static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
+                               uint32_t finalize_nbins, uint32_t list_mode, uint32_t count, bool by_values,
+                               bool build_value_table, void *ws, hipStream_t s)
+{
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
     qp_stats_t *stats_dev = reinterpret_cast<qp_stats_t *>(w + kOffStats);
     uint32_t *round_tickets = reinterpret_cast<uint32_t *>(w + kOffRoundTickets);
+    uint32_t *value_counts = reinterpret_cast<uint32_t *>(w + kOffValueCounts);
+    double *scores_by_j = reinterpret_cast<double *>(w + kOffScores);
+    double *scores_list = list_mode == kListFull ? scores_by_j : reinterpret_cast<double *>(w + kOffListScores);
+    qp_search_result_t *res = reinterpret_cast<qp_search_result_t *>(w + kOffResult);
 
     FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                      reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
     if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
-    uint32_t *value_counts = reinterpret_cast<uint32_t *>(w + kOffValueCounts);
-    hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, stats_dev, st ? st->mean : 0.0,
-                       st ? st->mad : 0.0, st ? st->b_r : 0.0, st ? 0 : 1, bits, t_steps, F, n, cands, ctl, round_tickets,
-                       fin, by_values ? value_counts : nullptr);
+    const ModelArgs m = model_args(plan, st, list_mode, count);
+    hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, m, stats_dev, n, cands, ctl, round_tickets, fin,
+                       (by_values && build_value_table) ? value_counts : nullptr, res, scores_by_j);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    SearchArgs a{x, n, cands, t_steps + 1u, cpr, (float)((1u << bits) - 1u),
-                 reinterpret_cast<double *>(w + kOffSearchPart), reinterpret_cast<double *>(w + kOffScores), ctl,
-                 round_tickets, reinterpret_cast<qp_search_result_t *>(w + kOffResult),
-                 reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n};
+    const uint32_t cpr = plan.cpr;
+    SearchArgs a{x, n, cands, count, cpr, (float)((1u << plan.bits) - 1u),
+                 reinterpret_cast<double *>(w + kOffSearchPart), scores_list, ctl, round_tickets, res,
+                 reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n, scores_by_j};
     if (by_values) {
-        const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;               // 16-byte vectors per block step
-        uint64_t chunks = ((n / 8) + tile - 1) / tile;
-        chunks = (chunks + 7) / 8 * 8;                                        // whole groups of 8 (one per XCD)
-        if (chunks > 256) chunks = 256;
-        hipLaunchKernelGGL(k_value_hist_bf16, dim3((uint32_t)(2 * chunks)), dim3(kVhThreads), 0, s,
-                           static_cast<const uint16_t *>(x), n, value_counts);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        if (build_value_table) {
+            const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;               // 16-byte vectors per block step
+            uint64_t chunks = ((n / 8) + tile - 1) / tile;
+            chunks = (chunks + 7) / 8 * 8;                                        // whole groups of 8 (one per XCD)
+            if (chunks > 256) chunks = 256;
+            hipLaunchKernelGGL(k_value_hist_bf16, dim3((uint32_t)(2 * chunks)), dim3(kVhThreads), 0, s,
+                               static_cast<const uint16_t *>(x), n, value_counts);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
         a.x = value_counts;
         a.n = kNumValues16;
         return cpr <= 16u ? launch_variant<kValues16, 16>(a, cpr, s) : launch_variant<kValues16, 32>(a, cpr, s);
@@ -542,6 +509,27 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, uint32_t bits, ui
     if (cpr <= 16u)
         return dtype == QP_F32 ? launch_variant<QP_F32, 16>(a, cpr, s) : launch_variant<QP_BF16, 16>(a, cpr, s);
     return dtype == QP_F32 ? launch_variant<QP_F32, 32>(a, cpr, s) : launch_variant<QP_BF16, 32>(a, cpr, s);
+}
+
+hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
+                         uint32_t finalize_nbins, void *ws, hipStream_t s)
+{
+    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
+    // them once (one pass over the tensor) and run the candidates over the value table.
+    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
+    // other small and medium tensors: one candidate per lane over LDS tiles
+    if (!by_values && tile_search_eligible(n, plan)) return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
+    // The coarse-to-fine sweep is only offered where the tile search runs it (see coarse_to_fine_supported):
+    // on this kernel it faulted the GPU once and the cause has not been found, so it is refused here.
+    if (plan.stride > 1u) return hipErrorInvalidValue;
+    return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, by_values, true, ws, s);
+}
+
+// Whether a coarse-to-fine search of such a tensor is available: only where the tile search handles it.
+bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan)
+{
+    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
+    return !by_values && tile_search_eligible(n, plan);
 }
 
 }  // namespace qp

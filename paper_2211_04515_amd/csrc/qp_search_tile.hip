@@ -35,15 +35,14 @@ struct TileSearchArgs {
     const void *x;
     uint64_t n;
     uint64_t share;          // elements per block, a multiple of 4
-    uint32_t bits, t_steps;
-    double F;
-    double mean_h, b_e_h, b_r_h;   // statistics from the host (from_ws == 0)
-    int from_ws;
+    ModelArgs m;             // the model and this sweep's candidate list
     FinalizeArgs fin;        // fin.nbins != 0: the statistics passes left partials only
     qp_stats_t *stats_dev;
     Cand *cands;
     Ctl *ctl;
-    double *partials;        // [t_steps + 1][gridDim.x]
+    const qp_search_result_t *prev;   // the coarse winner, read before a fine sweep
+    double *scores_by_j;
+    double *partials;        // [m.count][gridDim.x]
 };
 
 template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(TileSearchArgs a)
@@ -55,7 +54,7 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
 
     const uint32_t tid = threadIdx.x;
     const uint32_t G = gridDim.x, blk = blockIdx.x;
-    const uint32_t ncand = a.t_steps + 1u;
+    const uint32_t ncand = a.m.count;
     const uint64_t e_begin = (uint64_t)blk * a.share;
     const uint64_t e_end = min(a.n, e_begin + a.share);
 
@@ -76,52 +75,19 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
     // the first sub-tile is requested before the statistics are touched
     load_sub(e_begin);
 
-    // ---- statistics record and candidate table ----
+    // ---- statistics record and candidate table (every block the same values in the same order) ----
+    const qp_stats_t *st = nullptr;
     if (a.fin.nbins) {
         finalize_stats_block(a.fin.part1, a.fin.nb1, a.fin.part2, a.fin.nb2, a.fin.hist, a.fin.nbins, a.n, &sh_st);
         if (blk == 0 && tid == 0) *a.stats_dev = sh_st;
+        st = &sh_st;
+    } else if (a.m.from_ws) {
+        st = a.stats_dev;
     }
-    double mean = a.mean_h, b_e = a.b_e_h, b_r = a.b_r_h;
-    if (a.fin.nbins) {
-        mean = sh_st.mean;
-        b_e = sh_st.mad;
-        b_r = sh_st.b_r;
-    } else if (a.from_ws) {
-        mean = a.stats_dev->mean;
-        b_e = a.stats_dev->mad;
-        b_r = a.stats_dev->b_r;
-    }
-    double step = (b_r - b_e) / (double)a.t_steps;
-    {
-        const bool ok = (b_e > 0.0) && (b_r > 0.0) && isfinite(b_r) && isfinite(b_e) && isfinite(step);
-        if (!ok) step = 0.0;   // the grid collapses onto b_E
-    }
-    const float Lf = (float)((1u << a.bits) - 1u);
-    int safe = 1;
-    if (tid < ncand) {
-        const double b_j = b_e + (double)tid * step;
-        Cand c;
-        make_grid(mean, a.F * b_j, a.bits, c.lo, c.hi, c.scale, c.inv_scale);
-        sh_cands[tid] = c;
-        if (blk == 0) a.cands[tid] = c;
-        // With x clamped to [lo, hi], the level is at most rint(fl(fl(hi - lo) * inv_scale)); if that is
-        // at most L for every candidate, the clamp of the rounded level can never act and is dropped.
-        const float topl = rintf((c.hi - c.lo) * c.inv_scale);
-        if (!(isfinite(c.lo) && isfinite(c.hi) && topl >= 0.0f && topl <= Lf)) safe = 0;
-    }
-    safe = __syncthreads_and(safe);
-    if (blk == 0 && tid == 0) {
-        a.ctl->ticket_search = 0u;
-        a.ctl->short_seq = (uint32_t)safe;
-        a.ctl->b_e = b_e;
-        a.ctl->b_r = b_r;
-        a.ctl->step = step;
-        a.ctl->F = a.F;
-        a.ctl->mean = mean;
-        a.ctl->bits = a.bits;
-        a.ctl->t_steps = a.t_steps;
-        a.ctl->n = a.n;
-    }
+    const uint32_t j1 = (a.m.list_mode == kListFine) ? a.prev->j_star : 0u;
+    const int safe = setup_candidates(a.m, st, j1, a.n, sh_cands, blk == 0 ? a.cands : nullptr, blk == 0 ? a.ctl : nullptr,
+                                      blk == 0 ? a.scores_by_j : nullptr);
+    const float Lf = (float)((1u << a.m.bits) - 1u);
 
     // ---- scoring: lane -> (slice of the sub-tile, candidate) ----
     const uint32_t S = kStThreads / ncand;            // slices, >= 2
@@ -185,7 +151,8 @@ constexpr int kPkThreadsPick = 256;
 __global__ __launch_bounds__(kPkThreadsPick) void k_search_pick(const double *__restrict__ partials, uint32_t nblocks,
                                                                 double *__restrict__ scores, Ctl *__restrict__ ctl,
                                                                 qp_search_result_t *__restrict__ res,
-                                                                qp_qparams_t *__restrict__ best, uint64_t n)
+                                                                qp_qparams_t *__restrict__ best, uint64_t n,
+                                                                double *__restrict__ scores_by_j)
 {
     __shared__ double sh[kStMaxCands];
     __shared__ uint32_t sh_flag;
@@ -210,78 +177,72 @@ __global__ __launch_bounds__(kPkThreadsPick) void k_search_pick(const double *__
     for (uint32_t j = tid; j < ncand; j += kPkThreadsPick) sh[j] = ld_dev(&scores[j]);
     __syncthreads();
     if (wave != 0) return;
-    const uint32_t bj = first_min_wave(sh, ncand, lane);
-    if (lane == 0) {
-        qp_search_result_t r;
-        r.b_e = ctl->b_e;
-        r.b_r = ctl->b_r;
-        r.b_star = ctl->b_e + (double)bj * ctl->step;
-        r.alpha_star = ctl->F * r.b_star;
-        r.mse_aciq = sh[0] / (double)n;
-        r.mse_star = sh[bj] / (double)n;
-        r.j_star = bj;
-        r.t_steps = ncand - 1u;
-        *res = r;
-        qp_qparams_t q;
-        q.bits = ctl->bits;
-        q.reserved = 0u;
-        q.n = n;
-        make_grid(ctl->mean, r.alpha_star, ctl->bits, q.lo, q.hi, q.scale, q.inv_scale);
-        *best = q;
-        ctl->ticket_search = 0u;
-    }
+    const uint32_t bi = first_min_wave(sh, ncand, lane);
+    if (lane == 0) write_search_result(ctl, sh, ncand, bi, n, scores_by_j, res, best);
 }
 
-bool tile_search_eligible(uint64_t n, uint32_t t_steps)
+static uint32_t plan_max_count(const SearchPlan &plan)
 {
-    return t_steps + 1u <= kStMaxCands && n <= kTileSearchMaxN;
+    if (plan.stride <= 1u) return plan.t_steps + 1u;
+    const uint32_t coarse = (plan.t_steps + plan.stride - 1u) / plan.stride + 1u, fine = 2u * plan.stride - 1u;
+    return coarse > fine ? coarse : fine;
 }
 
-uint32_t tile_search_blocks(uint64_t n)
+bool tile_search_eligible(uint64_t n, const SearchPlan &plan)
 {
-    // shares of whole 128-element groups; as many blocks as shares of at least 512 elements allow
+    return n <= kTileSearchMaxN && plan_max_count(plan) <= kStMaxCands;
+}
+
+static uint64_t tile_share(uint64_t n)
+{
+    // shares of whole 128-element groups, at least 512 elements, at most kStMaxBlocks of them
     uint64_t share = (n + kStMaxBlocks - 1) / kStMaxBlocks;
     share = (share + 127) / 128 * 128;
-    if (share < 512) share = 512;
-    return ceil_div_u64(n, share);
+    return share < 512 ? 512 : share;
 }
 
-hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, uint32_t bits, uint32_t t_steps, double F,
-                              const qp_stats_t *st, uint32_t finalize_nbins, void *ws, hipStream_t s)
+uint32_t tile_search_blocks(uint64_t n) { return n <= kTileSearchMaxN ? ceil_div_u64(n, tile_share(n)) : 0u; }
+
+static hipError_t launch_tile_sweep(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
+                                    uint32_t finalize_nbins, uint32_t list_mode, uint32_t count, void *ws, hipStream_t s)
 {
-    if (!tile_search_eligible(n, t_steps)) return hipErrorInvalidValue;
     char *w = static_cast<char *>(ws);
     TileSearchArgs a;
     a.x = x;
     a.n = n;
-    uint64_t share = (n + kStMaxBlocks - 1) / kStMaxBlocks;
-    share = (share + 127) / 128 * 128;
-    if (share < 512) share = 512;
-    a.share = share;
-    a.bits = bits;
-    a.t_steps = t_steps;
-    a.F = F;
-    a.mean_h = st ? st->mean : 0.0;
-    a.b_e_h = st ? st->mad : 0.0;
-    a.b_r_h = st ? st->b_r : 0.0;
-    a.from_ws = st ? 0 : 1;
+    a.share = tile_share(n);
+    a.m = model_args(plan, st, list_mode, count);
     a.fin = FinalizeArgs{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                          reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
     if (finalize_nbins) stats_grid(n, dtype, a.fin.nb1, a.fin.nb2);
     a.stats_dev = reinterpret_cast<qp_stats_t *>(w + kOffStats);
     a.cands = reinterpret_cast<Cand *>(w + kOffCands);
     a.ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
+    a.prev = reinterpret_cast<const qp_search_result_t *>(w + kOffResult);
+    a.scores_by_j = reinterpret_cast<double *>(w + kOffScores);
     a.partials = reinterpret_cast<double *>(w + kOffSearchPart);
-    const uint32_t blocks = ceil_div_u64(n, share);
+    double *scores_list = list_mode == kListFull ? a.scores_by_j : reinterpret_cast<double *>(w + kOffListScores);
+    const uint32_t blocks = ceil_div_u64(n, a.share);
     if (dtype == QP_F32) hipLaunchKernelGGL(k_search_tile<QP_F32>, dim3(blocks), dim3(kStThreads), 0, s, a);
     else hipLaunchKernelGGL(k_search_tile<QP_BF16>, dim3(blocks), dim3(kStThreads), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_search_pick, dim3(t_steps + 1u), dim3(kPkThreadsPick), 0, s, a.partials, blocks,
-                       reinterpret_cast<double *>(w + kOffScores), a.ctl,
+    hipLaunchKernelGGL(k_search_pick, dim3(count), dim3(kPkThreadsPick), 0, s, a.partials, blocks, scores_list, a.ctl,
                        reinterpret_cast<qp_search_result_t *>(w + kOffResult),
-                       reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n);
+                       reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n, a.scores_by_j);
     return hipGetLastError();
+}
+
+hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
+                              uint32_t finalize_nbins, void *ws, hipStream_t s)
+{
+    if (!tile_search_eligible(n, plan)) return hipErrorInvalidValue;
+    if (plan.stride <= 1u)
+        return launch_tile_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, ws, s);
+    const uint32_t coarse = (plan.t_steps + plan.stride - 1u) / plan.stride + 1u;
+    hipError_t e = launch_tile_sweep(x, n, dtype, plan, st, finalize_nbins, kListCoarse, coarse, ws, s);
+    if (e != hipSuccess) return e;
+    return launch_tile_sweep(x, n, dtype, plan, st, 0u, kListFine, 2u * plan.stride - 1u, ws, s);
 }
 
 }  // namespace qp

@@ -878,3 +878,145 @@ def test_bf16_value_table_search_edge_cases(qp, kind):
         if res.j_star == ores.j_star:
             assert (q.lo, q.hi, q.scale, q.inv_scale, q.n) == (oq.lo, oq.hi, oq.scale, oq.inv_scale, n)
         assert res.mse_star == pytest.approx(scores[res.j_star] / n, rel=1e-15) or np.isnan(res.mse_star)
+
+
+# ----------------------------------------------------------------------------- variants of the search
+# (Gaussian model, ranges intersected with the data's, coarse-to-fine sweep) against their own oracle
+
+VARIANTS = [dict(dist=1), dict(clip=True), dict(stride=10), dict(clip=True, stride=7), dict(dist=1, clip=True, stride=10),
+            dict(stride=64), dict(stride=1, clip=True, dist=1)]
+# one input per search kernel: tile search (fp32, bf16), streaming search, bf16 value table
+VARIANT_INPUTS = [("C3", 300_007), ("C5", 200_003), ("C3", 2_600_011), ("C5", 1_300_001), ("C1", None)]
+
+
+def variant_cfg(qp, v, t=100):
+    cfg = qp.qp_default_search_cfg()
+    cfg.t_steps = t
+    cfg.dist = v.get("dist", 0)
+    cfg.flags = (qp.QP_SEARCH_CLIP_TO_DATA if v.get("clip") else 0) | (qp.QP_SEARCH_COARSE_TO_FINE if v.get("stride", 1) > 1 else 0)
+    cfg.coarse_stride = v.get("stride", 1) if v.get("stride", 1) > 1 else 0
+    return cfg
+
+
+def check_variant(qp, xf, st, bits, v, t, ws, res, q):
+    n = xf.size
+    ores, oq, oscores = orc.dsaciq_search_variant(xf, oracle_stats_from(st), bits, t, dist=v.get("dist", 0),
+                                                  clip_to_data=bool(v.get("clip")), stride=v.get("stride", 1))
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    scores = ws[off:off + 8 * (t + 1)].cpu().numpy().view(np.float64)
+    assert np.array_equal(np.isnan(scores), np.isnan(oscores))            # the same candidates were evaluated
+    tol = REL_SCORE if n < (1 << 19) else REL_SCORE_FULL
+    assert np.allclose(scores, oscores, rtol=tol, atol=0.0, equal_nan=True)
+    assert res.b_e == pytest.approx(ores.b_e, rel=1e-15) and res.b_r == pytest.approx(ores.b_r, rel=1e-15)
+    assert res.t_steps == t
+    if res.j_star != ores.j_star:   # only an exact numerical tie may differ
+        assert abs(oscores[res.j_star] - oscores[ores.j_star]) <= max(1e-12, tol) * oscores[ores.j_star]
+    else:
+        assert res.alpha_star == pytest.approx(ores.alpha_star, rel=1e-14)
+        assert (q.bits, q.n, q.lo, q.hi, q.scale, q.inv_scale) == (bits, n, oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        assert res.mse_star == pytest.approx(ores.mse_star, rel=tol)
+    assert res.mse_aciq == pytest.approx(ores.mse_aciq, rel=tol)
+    return ores
+
+
+def c2f_offered(x):
+    """The coarse-to-fine sweep exists only where the tile search runs it (fp32 up to 2^21 elements, bf16 below 2^20)."""
+    return x.size < (1 << 20) if x.dtype == np.uint16 else x.size <= (1 << 21)
+
+
+@pytest.mark.parametrize("name,n", VARIANT_INPUTS, ids=[f"{c[0]}_{c[1]}" for c in VARIANT_INPUTS])
+def test_search_variants_match_their_oracle(qp, name, n):
+    x = si.make_config(name, n=n)
+    xf = as_f32(x)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    for v in VARIANTS:
+        if v.get("stride", 1) > 1 and not c2f_offered(x):
+            continue      # refused by the library there: test_coarse_to_fine_is_refused_on_large_tensors
+        for bits in (2, 4):
+            print(f"[case] variant {v} {name} n={x.size} bits={bits}", flush=True)
+            cfg = variant_cfg(qp, v)
+            res, q = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=cfg)
+            check_variant(qp, xf, st, bits, v, 100, ws, res, q)
+
+
+def test_search_variants_other_step_counts_and_strides(qp):
+    x = si.make_config("C3", n=150_001)
+    xd = to_dev(x)
+    for t, stride in ((10, 30), (1, 2), (37, 5), (255, 16), (1000, 10), (100, 2)):
+        v = dict(stride=stride, clip=(t % 2 == 1))
+        cfg = variant_cfg(qp, v, t)
+        ws = qp.alloc_workspace(x.size, cfg)
+        st = qp.qp_stats(xd, ws)
+        print(f"[case] variant t={t} stride={stride}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, 4, ws, cfg=cfg)
+        check_variant(qp, x, st, 4, v, t, ws, res, q)
+
+
+def test_sender_path_with_variants(qp):
+    """qp_compress_async with a variant configuration: same bits as the step-by-step calls, payload = the oracle's."""
+    for name, n in (("C3", 400_003), ("C3", 2_300_001), ("C5", 1_250_003)):
+        x = si.make_config(name, n=n)
+        xf = as_f32(x)
+        xd = to_dev(x)
+        for v in (dict(clip=True), dict(dist=1, stride=10), dict(clip=True, stride=10)):
+            if v.get("stride", 1) > 1 and not c2f_offered(x):
+                continue
+            cfg = variant_cfg(qp, v)
+            print(f"[case] sender variant {v} {name} n={n}", flush=True)
+            ws = qp.alloc_workspace(n, cfg)
+            ws.fill_(0x6B)
+            packed = qp.alloc_packed(n, 4)
+            qp.qp_compress_async(xd, 4, ws, packed, cfg=cfg)
+            torch.cuda.synchronize()
+            st = qp.read_ws(ws, qp.QP_WS_STATS, qp.qp_stats_t)
+            res = qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)
+            q = qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)
+            check_variant(qp, xf, st, 4, v, 100, ws, res, q)
+            assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(xf, oracle_q_from(q)), 4))
+            ws2 = qp.alloc_workspace(n, cfg)
+            st2 = qp.qp_stats(xd, ws2)
+            res2, q2 = qp.qp_dsaciq_search(xd, st2, 4, ws2, cfg=cfg)
+            assert bytes(st) == bytes(st2) and bytes(res) == bytes(res2) and bytes(q) == bytes(q2)
+
+
+def test_clip_to_data_lowers_the_error_of_one_sided_data(qp):
+    x = si.make_config("C3", n=1_000_003)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    for bits in (2, 4):
+        r0, q0 = qp.qp_dsaciq_search(xd, st, bits, ws)
+        r1, q1 = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=variant_cfg(qp, dict(clip=True)))
+        assert r1.mse_star < 0.85 * r0.mse_star and q1.lo == np.float32(st.min)
+
+
+def test_coarse_to_fine_is_refused_on_large_tensors(qp):
+    """Above the tile search's limit the coarse-to-fine sweep is switched off (it returns an error before
+    anything is launched); the full sweep with the same other settings still runs."""
+    for name, n in (("C3", 2_600_011), ("C5", 1_300_001)):
+        x = si.make_config(name, n=n)
+        xd = to_dev(x)
+        ws = qp.alloc_workspace(x.size)
+        st = qp.qp_stats(xd, ws)
+        with pytest.raises(qp.QuantPipeError) as e:
+            qp.qp_dsaciq_search(xd, st, 4, ws, cfg=variant_cfg(qp, dict(stride=10)))
+        assert e.value.status == qp.QP_EINVAL
+        packed = qp.alloc_packed(x.size, 4)
+        with pytest.raises(qp.QuantPipeError):
+            qp.qp_compress_async(xd, 4, ws, packed, cfg=variant_cfg(qp, dict(stride=10, clip=True)))
+        res, q = qp.qp_dsaciq_search(xd, st, 4, ws, cfg=variant_cfg(qp, dict(clip=True)))
+        check_variant(qp, as_f32(x), st, 4, dict(clip=True), 100, ws, res, q)
+
+
+@pytest.mark.skip(reason="the coarse-to-fine sweep on the streaming search kernel (fp32 tensors above 2^21 elements) faulted the "
+                         "GPU once; a CPU emulation of the same launch under ASan/UBSan is clean and the cause has not been "
+                         "found, so the library refuses this case and it must not run on a GPU until a cause is shown")
+def test_coarse_to_fine_on_the_streaming_kernel(qp):
+    x = si.make_config("C3", n=2_600_011)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    res, q = qp.qp_dsaciq_search(xd, st, 2, ws, cfg=variant_cfg(qp, dict(stride=10)))
+    check_variant(qp, x, st, 2, dict(stride=10), 100, ws, res, q)

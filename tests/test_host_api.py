@@ -44,7 +44,7 @@ def test_library_exports_every_declared_symbol(qp):
 def test_struct_sizes_match_the_header_layout(qp):
     assert C.sizeof(qp.qp_stats_t) == 88
     assert C.sizeof(qp.qp_qparams_t) == 32
-    assert C.sizeof(qp.qp_search_cfg_t) == 16
+    assert C.sizeof(qp.qp_search_cfg_t) == 24
     assert C.sizeof(qp.qp_search_result_t) == 56
     offs = [qp.qp_ws_offset(r) for r in range(6)]
     assert offs == sorted(offs) and len(set(offs)) == 6 and all(o % 16 == 0 for o in offs)
@@ -61,7 +61,7 @@ def test_packed_bytes(qp):
 
 def test_workspace_bytes(qp):
     cfg = qp.qp_default_search_cfg()
-    assert (cfg.t_steps, cfg.cands_per_round, cfg.nbins, cfg.dist) == (100, 13, 2048, qp.QP_LAPLACE)
+    assert (cfg.t_steps, cfg.cands_per_round, cfg.nbins, cfg.dist, cfg.flags, cfg.coarse_stride) == (100, 13, 2048, qp.QP_LAPLACE, 0, 0)
     a = qp.qp_workspace_bytes(9_682_944)
     assert a == qp.qp_workspace_bytes(9_682_944, cfg) and a > qp.qp_ws_offset(qp.QP_WS_SCORES)
     cfg.t_steps = 1000
@@ -133,9 +133,14 @@ def test_argument_errors_are_reported_before_any_gpu_work(qp):
     assert L.qp_dsaciq_search(fake, 1000, 0, None, 4, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
     assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 5, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
     assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, None, fake, 1000, None, C.byref(res), C.byref(qo)) == qp.QP_ENOSPC
-    cfg = qp.qp_default_search_cfg()
-    cfg.dist = qp.QP_GAUSS
-    assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
+    for field, value in (("dist", 2), ("flags", 4), ("coarse_stride", 65), ("cands_per_round", 33), ("t_steps", 0)):
+        cfg = qp.qp_default_search_cfg()
+        setattr(cfg, field, value)
+        assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL, field
+    for field, value in (("dist", qp.QP_GAUSS), ("flags", qp.QP_SEARCH_CLIP_TO_DATA)):    # the histogram fit is the paper's form only
+        cfg = qp.qp_default_search_cfg()
+        setattr(cfg, field, value)
+        assert L.qp_dsaciq_hist_search_async(4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL, field
     cfg = qp.qp_default_search_cfg()
     cfg.t_steps = 5000
     assert L.qp_dsaciq_search_async(fake, 1000, 0, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
@@ -203,3 +208,33 @@ def test_next_bits_matches_oracle_and_the_papers_example(qp):
                 (1e6, 8, 64, 100, 0.0), (float("nan"), 8, 64, 100, 1e8), (1e6, 8, 64, 100, float("nan"))):
         with pytest.raises(qp.QuantPipeError):
             qp.qp_next_bits(*bad)
+
+
+def test_make_qparams_clipped_is_bit_identical_to_the_oracle(qp):
+    rng = np.random.default_rng(9)
+    for bits in BITS:
+        for _ in range(100):
+            center, alpha = float(rng.normal()), float(abs(rng.normal()) * 3)
+            lo, hi = sorted((float(rng.normal() * 2), float(rng.normal() * 2)))
+            if rng.random() < 0.3:
+                lo, hi = min(lo, center - 10), max(hi, center + 10)      # data range wider than the clipping range
+            a = qp.qp_make_qparams_clipped(center, alpha, lo, hi, bits, 31)
+            b = orc.make_qparams_clipped(center, alpha, lo, hi, bits, 31)
+            assert (a.bits, a.n, a.lo, a.hi, a.scale, a.inv_scale) == (b.bits, b.n, b.lo, b.hi, b.scale, b.inv_scale)
+    z = qp.qp_make_qparams_clipped(2.0, 1.0, 2.0, 2.0, 4, 3)
+    assert (z.lo, z.hi, z.scale, z.inv_scale) == (2.0, 2.0, 0.0, 0.0)
+    with pytest.raises(qp.QuantPipeError):
+        qp.qp_make_qparams_clipped(0.0, 1.0, -1.0, 1.0, 5, 1)
+
+
+def test_coarse_to_fine_is_refused_where_it_is_switched_off(qp):
+    """fp32 above 2^21 elements and bf16 from 2^20: QP_EINVAL before anything is launched (no GPU needed)."""
+    L = qp.lib()
+    fake, big = C.c_void_p(0x1000), 1 << 40
+    st, res, qo = qp.qp_stats_t(), qp.qp_search_result_t(), qp.qp_qparams_t()
+    cfg = qp.qp_default_search_cfg()
+    cfg.flags, cfg.coarse_stride = qp.QP_SEARCH_COARSE_TO_FINE, 10
+    for n, dtype in ((3_000_000, qp.QP_F32), ((1 << 21) + 1, qp.QP_F32), (1 << 20, qp.QP_BF16), (200_000_000, qp.QP_BF16)):
+        assert L.qp_dsaciq_search(fake, n, dtype, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
+        assert L.qp_dsaciq_search_async(fake, n, dtype, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
+        assert L.qp_compress_async(fake, n, dtype, 4, C.byref(cfg), fake, big, fake, big, None, None) == qp.QP_EINVAL
