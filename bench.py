@@ -41,7 +41,7 @@ NBUF = 16
 # HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload, scaled by
 # what the same counters read for plain device copies of the tensor in the same run (summary and
 # commands: profiles/hbm_traffic_C2_fp32.txt).  pack / unpack: mean over the six bitwidths.
-TRAFFIC_BYTES = {"search": 40.75e6, "pack": 46.61e6, "unpack": 46.75e6, "stats": 77.91e6}
+TRAFFIC_BYTES = {"search": 40.76e6, "pack": 46.61e6, "unpack": 46.75e6, "stats": 77.91e6}
 
 
 def main() -> int:
@@ -51,6 +51,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true", help="skip the 151M-element bf16 tensor leg")
+    ap.add_argument("--only-small", action="store_true",
+                    help="run only the 1x197x768 leg and print its figures (for a profile of the small-tensor path)")
+    ap.add_argument("--no-small", action="store_true",
+                    help="skip the 1x197x768 leg (it launches the same kernels on a small tensor, which would mix "
+                         "into a profiler's per-kernel averages)")
     ap.add_argument("--kernel-reps", type=int, default=64, help="back-to-back launches per kernel timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -69,6 +74,20 @@ def main() -> int:
         return 2
     qp.lib()
     torch.cuda.set_device(0)
+    if args.only_small:
+        def reps_small(fn, R=args.kernel_reps):
+            for r in range(4):
+                fn(r)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for r in range(R):
+                fn(r)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) * 1e3 / R
+        print(json.dumps({"small_tensor_fp32": small_tensor_leg(qp, si, torch, reps_small)}))
+        return 0
     name = "C2"
     bits_set = si.CONFIG_BITS[name]
     x_host = si.make_config(name)
@@ -198,7 +217,7 @@ def main() -> int:
         large = large_tensor_leg(qp, si, torch, timed_reps, args.kernel_reps)
 
     # one image's activations (1x197x768 fp32): the whole sender path per tensor, launch-bound
-    small = small_tensor_leg(qp, si, torch, timed_reps)
+    small = None if args.no_small else small_tensor_leg(qp, si, torch, timed_reps)
 
     cpu = None
     if not args.no_cpu_baseline:
