@@ -59,7 +59,7 @@ __device__ __host__ inline uint32_t list_index(uint32_t mode, uint32_t stride, u
 
 // Device-resident control block.
 struct Ctl {
-    uint32_t reserved0;
+    uint32_t ticket_stats;    // blocks of statistics pass 2 that have finished
     uint32_t ticket_search;   // rounds (or candidates) of the search that have finished
     uint32_t short_seq;       // 1: the search may drop the clamp of the rounded level
     uint32_t clip;            // 1: candidate ranges are intersected with [clip_lo, clip_hi]
@@ -421,6 +421,9 @@ __device__ inline qp_stats_t stats_record(const Part1 &a, const Part2 &b, uint32
     return st;
 }
 
+// DEV: the pass-2 partials and the histogram come from other blocks of the SAME kernel (the block
+// that draws pass 2's last ticket finalizes): they are read with device-coherent loads.
+template <bool DEV = false>
 __device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uint32_t nb1,
                                             const Part2 *__restrict__ part2, uint32_t nb2,
                                             const uint32_t *__restrict__ hist, uint32_t nbins, uint64_t n,
@@ -433,12 +436,14 @@ __device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uin
     const Part1 a = reduce_part1_block<kFinThreads>(part1, nb1, f1);
     Part2 q{0.0, 0.0};
     for (uint32_t i = tid; i < nb2; i += kFinThreads) {
-        const Part2 p = part2[i];
+        Part2 p;
+        if constexpr (DEV) p = Part2{ld_dev(&part2[i].dev), ld_dev(&part2[i].sq)};
+        else p = part2[i];
         q.dev += p.dev;
         q.sq += p.sq;
     }
     uint32_t peak = 0u;
-    for (uint32_t b = tid; b < nbins; b += kFinThreads) peak = max(peak, hist[b]);
+    for (uint32_t b = tid; b < nbins; b += kFinThreads) peak = max(peak, DEV ? ld_dev(&hist[b]) : hist[b]);
     q.dev = wave_sum(q.dev);
     q.sq = wave_sum(q.sq);
     peak = wave_max_u32(peak);
@@ -681,7 +686,6 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan);
 // The host's part of ModelArgs for one sweep of a plan.
 ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *stats_host_or_null, uint32_t list_mode, uint32_t count);
-hipError_t launch_stats_finalize(uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s);
 uint32_t search_blocks(uint64_t n);
 hipError_t launch_hist_search(uint32_t bits, uint32_t t_steps, double F, void *ws, hipStream_t s);
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *host_qp,

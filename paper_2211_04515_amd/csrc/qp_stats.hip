@@ -9,10 +9,12 @@
 // LDS slot per wave, then across blocks in a fixed order: no floating-point atomics, so
 // results are bit-reproducible from run to run.  Pass 2 needs mu, min and max; every block of
 // pass 2 re-reduces the (at most 512) pass-1 partials itself, with its first loads of the
-// tensor already in flight, which saves a launch and a grid-wide dependency.  A one-block
-// kernel after pass 2 (or the search's set-up kernel, when the search follows) turns the
-// partials and the histogram into the qp_stats_t record: kernel boundaries order the memory,
-// so neither pass needs a fence.
+// tensor already in flight, which saves a launch and a grid-wide dependency.  The partials and
+// the histogram become the qp_stats_t record either in the search that follows (the sender
+// path) or in the block of pass 2 that draws the last ticket.  That hand-over uses
+// device-coherent stores and loads plus a relaxed ticket, so it costs no cache write-back or
+// invalidation (with a release/acquire pair per block it cost more than a separate one-block
+// kernel; that kernel, 4 us and a launch gap, is what the ticket now saves).
 #include "qp_common.hpp"
 
 namespace qp {
@@ -55,7 +57,10 @@ __global__ __launch_bounds__(kS1Threads) void k_stats_pass1(const void *__restri
     // Clear what pass 2 and the search accumulate into (they run after this kernel on the stream).
     if (blockIdx.x == 0) {
         for (uint32_t b = tid; b < nbins; b += kS1Threads) hist[b] = 0u;
-        if (tid == 0) ctl->ticket_search = 0u;
+        if (tid == 0) {
+            ctl->ticket_search = 0u;
+            ctl->ticket_stats = 0u;
+        }
     }
 
     Acc1 a0{0.0, 0.0, INFINITY, -INFINITY, 0u};
@@ -122,7 +127,8 @@ template <int DT, int REP_SHIFT>
 __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restrict__ x, uint64_t n,
                                                             const Part1 *__restrict__ part1, uint32_t nb1,
                                                             Part2 *__restrict__ part2, uint32_t *__restrict__ hist,
-                                                            uint32_t nbins)
+                                                            uint32_t nbins, Ctl *__restrict__ ctl,
+                                                            qp_stats_t *__restrict__ out /* null: leave the partials */)
 {
     // The LDS histogram is kept in `rep` interleaved copies (copy = lane mod rep): lanes that hit the
     // same bin then update different addresses in different banks, which divides the serialisation
@@ -225,16 +231,27 @@ __global__ __launch_bounds__(kS2Threads) void k_stats_pass2(const void *__restri
             p.dev += sh2[w].dev;
             p.sq += sh2[w].sq;
         }
-        part2[blockIdx.x] = p;
+        if (out) {
+            st_dev(&part2[blockIdx.x].dev, p.dev);
+            st_dev(&part2[blockIdx.x].sq, p.sq);
+        } else {
+            part2[blockIdx.x] = p;
+        }
     }
-}
+    if (!out) return;
 
-__global__ __launch_bounds__(kFinThreads) void k_stats_finalize(const Part1 *__restrict__ part1, uint32_t nb1,
-                                                                const Part2 *__restrict__ part2, uint32_t nb2,
-                                                                const uint32_t *__restrict__ hist, uint32_t nbins,
-                                                                uint64_t n, qp_stats_t *__restrict__ out)
-{
-    finalize_stats_block(part1, nb1, part2, nb2, hist, nbins, n, out);
+    // ---- the last block to get here turns the partials into the record ----
+    __shared__ uint32_t sh_last;
+    wait_stores();     // this lane's histogram atomics and partial have arrived ...
+    __syncthreads();   // ... and so have those of every lane of the block
+    if (tid == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_stats, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_last = (prev == gridDim.x - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!sh_last) return;
+    finalize_stats_block<true>(part1, nb1, part2, gridDim.x, hist, nbins, n, out);
+    if (tid == 0) ctl->ticket_stats = 0u;
 }
 
 // Whole tiles per block: with T tiles and at most B blocks, every block takes ceil(T/B) tiles and
@@ -251,18 +268,6 @@ void stats_grid(uint64_t n, int dtype, uint32_t &nb1, uint32_t &nb2)
     nb2 = even_grid((nvec + kS2Threads * kS2Unroll - 1) / (kS2Threads * kS2Unroll), kMaxStat2Blocks);
 }
 
-hipError_t launch_stats_finalize(uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s)
-{
-    char *w = static_cast<char *>(ws);
-    uint32_t nb1, nb2;
-    stats_grid(n, dtype, nb1, nb2);
-    hipLaunchKernelGGL(k_stats_finalize, dim3(1), dim3(kFinThreads), 0, s, reinterpret_cast<const Part1 *>(w + kOffPart1),
-                       nb1, reinterpret_cast<const Part2 *>(w + kOffPart2), nb2,
-                       reinterpret_cast<const uint32_t *>(w + kOffHist), nbins, n,
-                       reinterpret_cast<qp_stats_t *>(w + kOffStats));
-    return hipGetLastError();
-}
-
 hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s, bool finalize)
 {
     char *w = static_cast<char *>(ws);
@@ -270,6 +275,7 @@ hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, vo
     Part2 *p2 = reinterpret_cast<Part2 *>(w + kOffPart2);
     uint32_t *hist = reinterpret_cast<uint32_t *>(w + kOffHist);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
+    qp_stats_t *out = finalize ? reinterpret_cast<qp_stats_t *>(w + kOffStats) : nullptr;
     uint32_t nb1, nb2;
     stats_grid(n, dtype, nb1, nb2);
     if (dtype == QP_F32)
@@ -277,7 +283,7 @@ hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, vo
     else
         hipLaunchKernelGGL(k_stats_pass1<QP_BF16>, dim3(nb1), dim3(kS1Threads), 0, s, x, n, p1, hist, nbins, ctl);
 #define QP_PASS2(DT, R) \
-    hipLaunchKernelGGL((k_stats_pass2<DT, R>), dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins)
+    hipLaunchKernelGGL((k_stats_pass2<DT, R>), dim3(nb2), dim3(kS2Threads), 0, s, x, n, p1, nb1, p2, hist, nbins, ctl, out)
     const uint32_t rs = hist_rep_shift(nbins);
     if (dtype == QP_F32) {
         if (rs == 3) QP_PASS2(QP_F32, 3); else if (rs == 2) QP_PASS2(QP_F32, 2); else QP_PASS2(QP_F32, 1);
@@ -285,9 +291,7 @@ hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, vo
         if (rs == 3) QP_PASS2(QP_BF16, 3); else if (rs == 2) QP_PASS2(QP_BF16, 2); else QP_PASS2(QP_BF16, 1);
     }
 #undef QP_PASS2
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !finalize) return e;
-    return launch_stats_finalize(n, dtype, nbins, ws, s);
+    return hipGetLastError();
 }
 
 }  // namespace qp
