@@ -32,7 +32,10 @@ constexpr int kValues16 = 2;
 constexpr uint32_t kNumValues16 = 65536;
 // bf16 tensors at least this large are searched through their value table (counting the values and
 // searching 65536 of them costs about 30 us; the tile search passes that at about a million elements)
-constexpr uint64_t kValueTableMinN = 1ull << 20;
+#ifndef QP_VALUE_TABLE_MIN_N
+#define QP_VALUE_TABLE_MIN_N (1ull << 20)
+#endif
+constexpr uint64_t kValueTableMinN = QP_VALUE_TABLE_MIN_N;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 

@@ -1,0 +1,155 @@
+"""The library's kernel sources, compiled by the host compiler against a CPU stand-in for the HIP runtime
+(tests/emu/) and run under AddressSanitizer + UBSan on tiny tensors, against the oracle.
+
+What this adds to the GPU parity tests: it runs without a GPU, and the sanitizers see every access of every
+kernel against buffers of exactly the sizes the C ABI asks for (workspace, packed stream), so an index
+that strays fails here first.  What it cannot show: speed, and races between blocks (they run one after
+the other).  The emulation is test infrastructure; the library has no CPU path."""
+import ctypes as C
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import qp_oracle as orc
+
+sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "emu"))
+import build_emu  # noqa: E402
+
+REL = 1e-11
+
+
+class Stats(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("n_nonfinite", C.c_uint64), ("mean", C.c_double), ("mad", C.c_double),
+                ("abs_mean", C.c_double), ("var", C.c_double), ("min", C.c_double), ("max", C.c_double),
+                ("nbins", C.c_uint32), ("peak_count", C.c_uint32), ("peak_density", C.c_double), ("b_r", C.c_double)]
+
+
+class QParams(C.Structure):
+    _fields_ = [("bits", C.c_uint32), ("reserved", C.c_uint32), ("n", C.c_uint64), ("lo", C.c_float), ("hi", C.c_float),
+                ("scale", C.c_float), ("inv_scale", C.c_float)]
+
+
+class Result(C.Structure):
+    _fields_ = [("b_e", C.c_double), ("b_r", C.c_double), ("b_star", C.c_double), ("alpha_star", C.c_double),
+                ("mse_aciq", C.c_double), ("mse_star", C.c_double), ("j_star", C.c_uint32), ("t_steps", C.c_uint32)]
+
+
+@pytest.fixture(scope="module")
+def drivers():
+    try:
+        out = build_emu.build_all()
+    except subprocess.CalledProcessError as e:
+        pytest.fail("emulation build failed:\n" + e.stderr.decode()[-3000:])
+    if any(v is None for v in out.values()):
+        pytest.skip("no host clang++ to build the emulation with")
+    return out
+
+
+def start_driver(exe, out_dir, x, bits, t=100, dist=0, flags=0, stride=0, nbins=2048, cus=4):
+    os.makedirs(out_dir, exist_ok=True)
+    inp = os.path.join(out_dir, "in.bin")
+    x.tofile(inp)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    return subprocess.run([exe, inp, str(x.size), "1" if x.dtype == np.uint16 else "0", str(bits), str(t), str(dist),
+                           str(flags), str(stride), str(nbins), str(cus), out_dir], capture_output=True, env=env, timeout=900)
+
+
+def read_outputs(p, out_dir):
+    assert p.returncode == 0, "sanitizer report or crash:\n" + p.stderr.decode()[-4000:]
+    path = lambda name: os.path.join(out_dir, name)
+    rc = [int(v) for v in open(path("status.txt")).read().split()]
+    rd = lambda name, dt: np.fromfile(path(name), dtype=dt)
+    return dict(rc=rc, stats=Stats.from_buffer_copy(open(path("stats.bin"), "rb").read()),
+                res=Result.from_buffer_copy(open(path("result.bin"), "rb").read()),
+                q=QParams.from_buffer_copy(open(path("qparams.bin"), "rb").read()),
+                hist=rd("hist.bin", np.uint32), scores=rd("scores.bin", np.float64), packed=rd("packed.bin", np.uint8),
+                y=rd("y.bin", np.float32))
+
+
+def check_against_oracle(r, x, bits, t=100, dist=0, clip=False, stride=1, nbins=2048):
+    xf = orc.widen_bf16(x) if x.dtype == np.uint16 else x
+    n = x.size
+    assert r["rc"] == [0, 0, 0, 0, 0, 1]        # every call succeeded; the fused sender path equals the step-by-step calls
+    st = r["stats"]
+    rc, ref, hist_ref = orc.stats(xf, nbins=nbins, want_hist=True)
+    assert (st.n, st.n_nonfinite, st.min, st.max, st.nbins, st.peak_count) == (n, 0, ref.min, ref.max, nbins, ref.peak_count)
+    for f in ("mean", "mad", "abs_mean", "var"):
+        a, b = getattr(st, f), getattr(ref, f)
+        assert abs(a - b) <= REL * max(abs(b), ref.abs_mean * 1e-3 if f == "mean" else 0.0), f
+    assert np.array_equal(r["hist"], hist_ref[:nbins])
+    ost = orc.Stats()
+    for name, _ in orc.Stats._fields_:
+        setattr(ost, name, getattr(st, name))
+    ores, oq, oscores = orc.dsaciq_search_variant(xf, ost, bits, t, dist=dist, clip_to_data=clip, stride=stride)
+    assert np.array_equal(np.isnan(r["scores"]), np.isnan(oscores))
+    assert np.allclose(r["scores"], oscores, rtol=REL, atol=0.0, equal_nan=True)
+    res, q = r["res"], r["q"]
+    assert res.j_star == ores.j_star and res.t_steps == t
+    assert res.alpha_star == pytest.approx(ores.alpha_star, rel=1e-14)
+    assert (q.bits, q.n, q.lo, q.hi, q.scale, q.inv_scale) == (bits, n, oq.lo, oq.hi, oq.scale, oq.inv_scale)
+    codes = orc.quantize(xf, oq)
+    assert np.array_equal(r["packed"], orc.pack(codes, bits))
+    assert np.array_equal(r["y"], orc.dequantize(codes, oq))
+
+
+def small_input(kind, n):
+    if kind == "bf16":
+        return si.make_config("C5", n=n)
+    return si.make_config(kind, n=n)
+
+
+# (kind, n, bits, variant, t): one case sweeps the paper's t = 100, the others a shorter grid (one emulated block
+# per candidate in the pick kernel makes t the main cost here)
+TILE_CASES = [("C1", 3_011, 2, {}, 100), ("C3", 4_999, 3, {}, 12), ("bf16", 5_345, 4, {}, 12), ("C2", 4_097, 16, {}, 7),
+              ("C3", 130, 6, {}, 12), ("C3", 3_001, 4, dict(clip=True), 12), ("C2", 2_191, 2, dict(dist=1, stride=4), 20),
+              ("bf16", 2_777, 8, dict(stride=3, clip=True), 12), ("C1", 5, 4, {}, 5), ("C3", 1, 8, {}, 3)]
+# the same kind of tensors through the kernels large tensors take (thresholds lowered at build time)
+STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37), ("bf16", 5_001, 4, {}, 30),
+                ("bf16", 3_000, 3, dict(dist=1), 20), ("C1", 2_049, 6, {}, 1)]
+REFUSED = ("C3", 5_000, 4, dict(stride=10), 100)
+ALL_CASES = [("default", c) for c in TILE_CASES] + [("streaming", c) for c in STREAM_CASES] + [("streaming", REFUSED)]
+
+
+def case_id(tag, c):
+    return f"{tag}-{c[0]}_{c[1]}_k{c[2]}_t{c[4]}" + "".join(f"_{k}{v}" for k, v in sorted(c[3].items()))
+
+
+@pytest.fixture(scope="module")
+def runs(drivers, tmp_path_factory):
+    """Every case's driver run, started together (each run is one process with a thread per emulated lane)."""
+    from concurrent.futures import ThreadPoolExecutor
+    base = str(tmp_path_factory.mktemp("emu"))
+
+    def go(item):
+        tag, (kind, n, bits, v, t) = item
+        x = small_input(kind, n)
+        flags = (1 if v.get("clip") else 0) | (2 if v.get("stride", 1) > 1 else 0)
+        out_dir = os.path.join(base, case_id(tag, item[1]))
+        p = start_driver(drivers[tag], out_dir, x, bits, t=t, dist=v.get("dist", 0), flags=flags,
+                         stride=v.get("stride", 0) if flags & 2 else 0, cus=4 if tag == "default" else 2)
+        return case_id(tag, item[1]), (p, out_dir, x)
+
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        return dict(ex.map(go, ALL_CASES))
+
+
+@pytest.mark.parametrize("tag,case", [a for a in ALL_CASES if a[1] is not REFUSED], ids=[case_id(*a) for a in ALL_CASES if a[1] is not REFUSED])
+def test_whole_path_on_the_emulation(runs, tag, case):
+    """Statistics, search (tile search with the default thresholds; streaming search with rounds and tickets and,
+    for bf16 of at least 4096 elements, the value table with the lowered ones), quantize+pack, unpack+dequantize
+    and the fused sender path: sanitizer-clean and equal to the oracle."""
+    kind, n, bits, v, t = case
+    p, out_dir, x = runs[case_id(tag, case)]
+    r = read_outputs(p, out_dir)
+    check_against_oracle(r, x, bits, t=t, dist=v.get("dist", 0), clip=bool(v.get("clip")), stride=v.get("stride", 1))
+
+
+def test_emulation_refuses_what_the_library_refuses(runs):
+    """Coarse-to-fine is switched off outside the tile search: the search returns QP_EINVAL and nothing more runs."""
+    p, out_dir, x = runs[case_id("streaming", REFUSED)]
+    r = read_outputs(p, out_dir)
+    assert r["rc"][0] == 0 and r["rc"][1] == -1
