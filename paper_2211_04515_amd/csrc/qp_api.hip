@@ -199,7 +199,7 @@ qp_status qp_make_qparams_clipped(double center, double alpha, double data_min, 
 
 static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, const qp_stats_t *stats, uint32_t bits,
                                const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream,
-                               uint32_t finalize_nbins = 0)
+                               uint32_t finalize_nbins = 0, bool value_table_ready = false)
 {
     if (!x_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || !bits_ok(bits) || !aligned16(x_dev)) return QP_EINVAL;
     if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
@@ -207,7 +207,8 @@ static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, co
     if (w != QP_OK) return w;
     const SearchPlan plan = make_plan(bits, cfg);
     if (plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;   // see quantpipe.h
-    return hip_status(launch_search(x_dev, n, dtype, plan, stats, finalize_nbins, ws_dev, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_search(x_dev, n, dtype, plan, stats, finalize_nbins, value_table_ready, ws_dev,
+                                    static_cast<hipStream_t>(stream)));
 }
 
 qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
@@ -326,10 +327,12 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
         const SearchPlan plan = make_plan(bits, cfg);
         if (plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;
     }
-    // the two statistics passes leave partials; the search finalizes them itself
+    // The two statistics passes leave partials and the search finalizes them itself; a large bf16 tensor goes
+    // through its value table instead, which the statistics build and finalize and the search then reuses.
+    const bool table = uses_value_table(n, dtype);
     st = hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), false));
     if (st != QP_OK) return st;
-    st = search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream, nbins);
+    st = search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream, table ? 0u : nbins, table);
     if (st != QP_OK) return st;
     const qp_qparams_t *qdev = reinterpret_cast<const qp_qparams_t *>(static_cast<char *>(ws_dev) + kOffQParams);
     st = qp_quant_pack_dev(x_dev, n, dtype, bits, qdev, packed_dev, packed_bytes, stream);

@@ -16,6 +16,13 @@ constexpr uint32_t kMaxCandsPerRound = 32;
 constexpr uint32_t kMaxStat1Blocks = 512;  // most blocks of statistics pass 1 (256 lanes each)
 constexpr uint32_t kMaxStat2Blocks = 256;  // most blocks of pass 2 (512 lanes each): one per CU measured best
 constexpr uint32_t kMaxSearchBlocks = 1024;
+constexpr uint32_t kNumValues16 = 65536;   // bit patterns of a bfloat16
+// bf16 tensors at least this large go through their value table (counting the values and working on
+// 65536 of them costs about 30 us; the per-element kernels pass that at about a million elements)
+#ifndef QP_VALUE_TABLE_MIN_N
+#define QP_VALUE_TABLE_MIN_N (1ull << 20)
+#endif
+constexpr uint64_t kValueTableMinN = QP_VALUE_TABLE_MIN_N;
 
 // Per-block partial of the first statistics pass.
 struct Part1 {
@@ -682,7 +689,12 @@ void stats_grid(uint64_t n, int dtype, uint32_t &nb1, uint32_t &nb2);
 // workspace; finalize_nbins != 0: the search first finalizes the statistics that
 // launch_stats(..., finalize = false) left as partials (histogram of finalize_nbins bins).
 hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *stats_host_or_null,
-                         uint32_t finalize_nbins, void *ws, hipStream_t s);
+                         uint32_t finalize_nbins, bool value_table_ready, void *ws, hipStream_t s);
+// Large bf16 tensors: the table of value counts (zeroed and built in one pass over the tensor) and the
+// statistics record and histogram computed from it.
+bool uses_value_table(uint64_t n, int dtype);
+hipError_t launch_value_table(const void *x, uint64_t n, void *ws, hipStream_t s);
+hipError_t launch_stats_from_table(uint64_t n, uint32_t nbins, void *ws, hipStream_t s);
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan);
 // The host's part of ModelArgs for one sweep of a plan.
 ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *stats_host_or_null, uint32_t list_mode, uint32_t count);

@@ -29,13 +29,6 @@ namespace qp {
 // x points at their counts (see k_value_hist_bf16); element i has the value of pattern i and the
 // weight counts[i].
 constexpr int kValues16 = 2;
-constexpr uint32_t kNumValues16 = 65536;
-// bf16 tensors at least this large are searched through their value table (counting the values and
-// searching 65536 of them costs about 30 us; the tile search passes that at about a million elements)
-#ifndef QP_VALUE_TABLE_MIN_N
-#define QP_VALUE_TABLE_MIN_N (1ull << 20)
-#endif
-constexpr uint64_t kValueTableMinN = QP_VALUE_TABLE_MIN_N;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
@@ -46,13 +39,10 @@ constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vect
 __global__ __launch_bounds__(kFinThreads) void k_search_setup(ModelArgs m, qp_stats_t *__restrict__ stats_dev, uint64_t n,
                                                               Cand *__restrict__ cands, Ctl *__restrict__ ctl,
                                                               uint32_t *__restrict__ round_tickets, FinalizeArgs fin,
-                                                              uint32_t *__restrict__ value_counts,
                                                               const qp_search_result_t *__restrict__ prev,
                                                               double *__restrict__ scores_by_j)
 {
     for (uint32_t j = threadIdx.x; j <= kMaxT; j += blockDim.x) round_tickets[j] = 0u;
-    if (value_counts)   // the bf16 value table is accumulated with atomics by the next kernel
-        for (uint32_t j = threadIdx.x; j < kNumValues16; j += blockDim.x) value_counts[j] = 0u;
     if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
     const uint32_t j1 = (m.list_mode == kListFine) ? prev->j_star : 0u;
     setup_candidates(m, m.from_ws ? stats_dev : nullptr, j1, n, cands, nullptr, ctl, scores_by_j);
@@ -148,60 +138,6 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
             }
             score(v, w, (int)rem);
         }
-    }
-}
-
-// The value table of a bfloat16 tensor: counts[p] = number of elements with bit pattern p.  A
-// bf16 tensor has at most 65536 distinct values, and the error of an element under a candidate
-// depends on its value only, so the search can run over the table (65536 weighted "elements")
-// instead of the tensor: the same sum of squared errors, grouped by value.
-// A block counts one sign (32768 patterns, 128 KB of LDS, plain u32 counters) of one chunk of the
-// tensor; blocks b and b+8 sit on the same XCD (blocks are dealt round-robin to the 8 XCDs) and
-// take the two signs of the same chunk, so the second reader of a chunk hits in that XCD's L2.
-constexpr int kVhThreads = 1024;
-constexpr int kVhUnroll = 4;
-__global__ __launch_bounds__(kVhThreads) void k_value_hist_bf16(const uint16_t *__restrict__ x, uint64_t n,
-                                                                uint32_t *__restrict__ counts)
-{
-    __shared__ uint32_t sh[32768];
-    const uint32_t tid = threadIdx.x;
-    const uint32_t sign = (blockIdx.x >> 3) & 1u;
-    const uint32_t chunk = ((blockIdx.x >> 4) << 3) | (blockIdx.x & 7u);
-    const uint32_t nchunks = gridDim.x / 2;
-    for (uint32_t i = tid; i < 32768u; i += kVhThreads) sh[i] = 0u;
-    __syncthreads();
-    auto count = [&](uint32_t h) {
-        if ((h >> 15) == sign) atomicAdd(&sh[h & 0x7fffu], 1u);
-    };
-    const uint64_t nvec = n / 8;   // 16-byte vectors of 8 elements
-    const uint4 *__restrict__ x16 = reinterpret_cast<const uint4 *>(x);
-    const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;
-    uint64_t base = (uint64_t)chunk * tile;
-    const uint64_t stride = (uint64_t)nchunks * tile;
-    for (; base < nvec; base += stride) {
-        uint4 v[kVhUnroll];
-#pragma unroll
-        for (int u = 0; u < kVhUnroll; ++u) {
-            const uint64_t i = base + (uint64_t)u * kVhThreads + tid;
-            v[u] = (i < nvec) ? x16[i] : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < kVhUnroll; ++u) {
-            if (base + (uint64_t)u * kVhThreads + tid < nvec) {
-                const uint32_t wds[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    count(wds[k] & 0xffffu);
-                    count(wds[k] >> 16);
-                }
-            }
-        }
-    }
-    if (chunk == 0 && tid < (uint32_t)(n - nvec * 8)) count(x[nvec * 8 + tid]);
-    __syncthreads();
-    for (uint32_t i = tid; i < 32768u; i += kVhThreads) {
-        const uint32_t c = sh[i];
-        if (c) atomicAdd(&counts[(sign << 15) | i], c);
     }
 }
 
@@ -484,7 +420,7 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
     if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
     const ModelArgs m = model_args(plan, st, list_mode, count);
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, m, stats_dev, n, cands, ctl, round_tickets, fin,
-                       (by_values && build_value_table) ? value_counts : nullptr, res, scores_by_j);
+                       res, scores_by_j);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -494,13 +430,7 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
                  reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n, scores_by_j};
     if (by_values) {
         if (build_value_table) {
-            const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;               // 16-byte vectors per block step
-            uint64_t chunks = ((n / 8) + tile - 1) / tile;
-            chunks = (chunks + 7) / 8 * 8;                                        // whole groups of 8 (one per XCD)
-            if (chunks > 256) chunks = 256;
-            hipLaunchKernelGGL(k_value_hist_bf16, dim3((uint32_t)(2 * chunks)), dim3(kVhThreads), 0, s,
-                               static_cast<const uint16_t *>(x), n, value_counts);
-            e = hipGetLastError();
+            e = launch_value_table(x, n, ws, s);
             if (e != hipSuccess) return e;
         }
         a.x = value_counts;
@@ -515,23 +445,24 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
 }
 
 hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
-                         uint32_t finalize_nbins, void *ws, hipStream_t s)
+                         uint32_t finalize_nbins, bool value_table_ready, void *ws, hipStream_t s)
 {
     // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
     // them once (one pass over the tensor) and run the candidates over the value table.
-    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
+    const bool by_values = uses_value_table(n, dtype);
     // other small and medium tensors: one candidate per lane over LDS tiles
     if (!by_values && tile_search_eligible(n, plan)) return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
     // The coarse-to-fine sweep is only offered where the tile search runs it (see coarse_to_fine_supported):
     // on this kernel it faulted the GPU once and the cause has not been found, so it is refused here.
     if (plan.stride > 1u) return hipErrorInvalidValue;
-    return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, by_values, true, ws, s);
+    return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, by_values,
+                        !value_table_ready, ws, s);
 }
 
 // Whether a coarse-to-fine search of such a tensor is available: only where the tile search handles it.
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan)
 {
-    const bool by_values = (dtype == QP_BF16) && (n >= kValueTableMinN);
+    const bool by_values = uses_value_table(n, dtype);
     return !by_values && tile_search_eligible(n, plan);
 }
 

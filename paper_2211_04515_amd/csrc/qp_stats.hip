@@ -270,6 +270,10 @@ void stats_grid(uint64_t n, int dtype, uint32_t &nb1, uint32_t &nb2)
 
 hipError_t launch_stats(const void *x, uint64_t n, int dtype, uint32_t nbins, void *ws, hipStream_t s, bool finalize)
 {
+    if (uses_value_table(n, dtype)) {   // one pass over the tensor; the record is always finalized here
+        const hipError_t e = launch_value_table(x, n, ws, s);
+        return e != hipSuccess ? e : launch_stats_from_table(n, nbins, ws, s);
+    }
     char *w = static_cast<char *>(ws);
     Part1 *p1 = reinterpret_cast<Part1 *>(w + kOffPart1);
     Part2 *p2 = reinterpret_cast<Part2 *>(w + kOffPart2);
