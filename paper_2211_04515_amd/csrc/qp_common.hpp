@@ -192,19 +192,8 @@ template <int DT> __device__ __forceinline__ void load16_stream(const void *base
 // the block that draws the last ticket pays for the ACQUIRE (cache invalidation) before it
 // reads the others' partials.  An acquire in every block would invalidate the XCD's L2 under
 // the blocks still streaming the tensor.
-#ifndef QP_TICKET_MODE
-#define QP_TICKET_MODE 1
-#endif
-#if QP_TICKET_MODE == 0
-#define QP_TICKET_ORDER __ATOMIC_ACQ_REL
-#define QP_TICKET_ACQUIRE() ((void)0)
-#elif QP_TICKET_MODE == 1
 #define QP_TICKET_ORDER __ATOMIC_RELEASE
 #define QP_TICKET_ACQUIRE() __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent")
-#else   // timing probe only: no ordering at all, results are not valid
-#define QP_TICKET_ORDER __ATOMIC_RELAXED
-#define QP_TICKET_ACQUIRE() ((void)0)
-#endif
 
 // ---- device-coherent accesses ---------------------------------------------------------------
 // For data that blocks of one kernel hand to each other.  The L2 of an XCD is not coherent with
