@@ -51,6 +51,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true", help="skip the 151M-element bf16 tensor leg")
+    ap.add_argument("--no-c4", action="store_true", help="skip the microbatch-stream leg (32x257x1280 fp32 per microbatch)")
     ap.add_argument("--only-small", action="store_true",
                     help="run only the 1x197x768 leg and print its figures (for a profile of the small-tensor path)")
     ap.add_argument("--no-small", action="store_true",
@@ -219,6 +220,11 @@ def main() -> int:
     # one image's activations (1x197x768 fp32): the whole sender path per tensor, launch-bound
     small = None if args.no_small else small_tensor_leg(qp, si, torch, timed_reps)
 
+    # a stream of microbatches whose bitwidth follows a bandwidth trace: sustained time per microbatch
+    c4 = None
+    if not args.no_c4 and not args.no_large:
+        c4 = c4_stream_leg(qp, si, torch)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(x_host, bits_set)
@@ -239,6 +245,7 @@ def main() -> int:
         "per_bitwidth": per_bits,
         "large_tensor_bf16": large,
         "small_tensor_fp32": small,
+        "microbatch_stream_fp32": c4,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -273,6 +280,40 @@ def large_tensor_leg(qp, si, torch, timed_reps, reps):
             out["sender_path_us_per_tensor"] = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % nb]))
         del packs
     return out
+
+
+def c4_stream_leg(qp, si, torch, n_mb=48):
+    """Sender path + receiver per microbatch (32x257x1280 fp32, 42 MB), back to back on one stream, over a ring of
+    eight unit-Laplace buffers scaled per microbatch; the bitwidth of each microbatch follows the seeded bandwidth
+    trace.  All inputs are resident before the timed region."""
+    n = si.numel("C4")
+    stream = si.c4_stream(n_mb)
+    ring = [torch.from_numpy(si.unit_laplace(n, 100 + b)).cuda() for b in range(8)]
+    xs = [ring[buf] * b_m for (buf, b_m, bw, bits) in stream]          # 48 x 42 MB, all distinct
+    packs = {k: qp.alloc_packed(n, k) for k in sorted({s[3] for s in stream})}
+    ws = qp.alloc_workspace(n)
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    qdev = ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS)
+
+    def run():
+        for x, (_, _, _, bits) in zip(xs, stream):
+            qp.qp_compress_async(x, bits, ws, packs[bits])
+            qp.qp_unpack_dequant_dev(packs[bits], bits, qdev, y)
+
+    run()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    run()
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / n_mb
+    hist = {}
+    for s_ in stream:
+        hist[str(s_[3])] = hist.get(str(s_[3]), 0) + 1
+    return {"elements_per_microbatch": n, "microbatches": n_mb, "bitwidths_used": hist, "us_per_microbatch": us,
+            "activation_GBs": n * 4 / us / 1e3,
+            "timed": "statistics, DS-ACIQ (t = 100), quantize+pack, unpack+dequantize per microbatch, one stream, two HIP events"}
 
 
 def small_tensor_leg(qp, si, torch, timed_reps):
