@@ -194,6 +194,11 @@ def main() -> int:
     ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % NBUF], ws))
     # the histogram-fit reading of Eq. 1 works on the 2048-bin histogram only (no tensor pass)
     th = timed_reps(lambda r: qp.qp_dsaciq_hist_search_async(4, ws))
+    # beyond the paper: coarse-to-fine sweep (stride 10: 11 + 19 candidates instead of 101), same winner on one-valley curves
+    c2f = qp.qp_default_search_cfg()
+    c2f.flags, c2f.coarse_stride = qp.QP_SEARCH_COARSE_TO_FINE, 10
+    qp.qp_stats_async(xs[0], ws)
+    tc = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % NBUF], 4, ws, cfg=c2f))
 
     def hbm(kernel, byts, us, key):
         a = byts / us / 1e3
@@ -241,6 +246,7 @@ def main() -> int:
         "stage_us": {k: mean(v) for k, v in stage.items()},
         "dsaciq_us_per_tensor": search_us,
         "dsaciq_histogram_fit_us_per_tensor": th,
+        "dsaciq_coarse_to_fine_us_per_tensor": tc,
         "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
         "per_bitwidth": per_bits,
         "large_tensor_bf16": large,

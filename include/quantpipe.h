@@ -102,9 +102,9 @@ typedef struct {
  *                               result whenever the error curve has a single valley, with about
  *                               t/s + 2s evaluations instead of t + 1.  s = coarse_stride
  *                               (0 = 10; at most 64).  Scores of candidates that were never
- *                               evaluated are NaN in QP_WS_SCORES.  Available for fp32 tensors of
- *                               at most 2^21 elements and bf16 tensors of fewer than 2^20; larger
- *                               ones are refused with QP_EINVAL (use the full sweep). */
+ *                               evaluated are NaN in QP_WS_SCORES.  Not offered for bf16 tensors of
+ *                               2^20 elements or more (QP_EINVAL): those are searched through the
+ *                               table of their 65536 possible values, where the full sweep is cheap. */
 #define QP_SEARCH_CLIP_TO_DATA 1u
 #define QP_SEARCH_COARSE_TO_FINE 2u
 typedef struct {

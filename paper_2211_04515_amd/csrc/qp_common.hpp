@@ -694,6 +694,7 @@ hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits
 // The search with one candidate per lane over LDS-staged tiles, for tensors of at most
 // kTileSearchMaxN elements and at most 256 candidates (same arguments as launch_search).
 bool tile_search_eligible(uint64_t n, const SearchPlan &plan);
+bool tile_search_can_run(const SearchPlan &plan);
 uint32_t tile_search_blocks(uint64_t n);
 hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan,
                               const qp_stats_t *stats_host_or_null, uint32_t finalize_nbins, void *ws, hipStream_t s);

@@ -452,18 +452,23 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
     const bool by_values = uses_value_table(n, dtype);
     // other small and medium tensors: one candidate per lane over LDS tiles
     if (!by_values && tile_search_eligible(n, plan)) return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
-    // The coarse-to-fine sweep is only offered where the tile search runs it (see coarse_to_fine_supported):
-    // on this kernel it faulted the GPU once and the cause has not been found, so it is refused here.
-    if (plan.stride > 1u) return hipErrorInvalidValue;
+    // A coarse-to-fine sweep always runs on the tile search, whatever the size (its short candidate lists
+    // suit the one-candidate-per-lane layout; on this file's streaming kernel the sweep faulted the GPU once,
+    // cause not found, so it is not launched from here).
+    if (plan.stride > 1u) {
+        if (!coarse_to_fine_supported(n, dtype, plan)) return hipErrorInvalidValue;
+        return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
+    }
     return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, by_values,
                         !value_table_ready, ws, s);
 }
 
-// Whether a coarse-to-fine search of such a tensor is available: only where the tile search handles it.
+// Whether a coarse-to-fine search of such a tensor is available: wherever the tile search can take it.  Large
+// bf16 tensors are searched through their value table (a full sweep over 65536 entries costs about 20 us, so
+// there is nothing to gain) and are refused.
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan)
 {
-    const bool by_values = uses_value_table(n, dtype);
-    return !by_values && tile_search_eligible(n, plan);
+    return !uses_value_table(n, dtype) && tile_search_can_run(plan);
 }
 
 }  // namespace qp

@@ -188,9 +188,12 @@ static uint32_t plan_max_count(const SearchPlan &plan)
     return coarse > fine ? coarse : fine;
 }
 
+// the kernel takes a tensor of any size; above kTileSearchMaxN the streaming search is the faster one
+bool tile_search_can_run(const SearchPlan &plan) { return plan_max_count(plan) <= kStMaxCands; }
+
 bool tile_search_eligible(uint64_t n, const SearchPlan &plan)
 {
-    return n <= kTileSearchMaxN && plan_max_count(plan) <= kStMaxCands;
+    return n <= kTileSearchMaxN && tile_search_can_run(plan);
 }
 
 static uint64_t tile_share(uint64_t n)
@@ -201,7 +204,7 @@ static uint64_t tile_share(uint64_t n)
     return share < 512 ? 512 : share;
 }
 
-uint32_t tile_search_blocks(uint64_t n) { return n <= kTileSearchMaxN ? ceil_div_u64(n, tile_share(n)) : 0u; }
+uint32_t tile_search_blocks(uint64_t n) { return ceil_div_u64(n, tile_share(n)); }
 
 static hipError_t launch_tile_sweep(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
                                     uint32_t finalize_nbins, uint32_t list_mode, uint32_t count, void *ws, hipStream_t s)
@@ -236,7 +239,7 @@ static hipError_t launch_tile_sweep(const void *x, uint64_t n, int dtype, const 
 hipError_t launch_tile_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
                               uint32_t finalize_nbins, void *ws, hipStream_t s)
 {
-    if (!tile_search_eligible(n, plan)) return hipErrorInvalidValue;
+    if (!tile_search_can_run(plan)) return hipErrorInvalidValue;
     if (plan.stride <= 1u)
         return launch_tile_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, ws, s);
     const uint32_t coarse = (plan.t_steps + plan.stride - 1u) / plan.stride + 1u;

@@ -920,8 +920,9 @@ def check_variant(qp, xf, st, bits, v, t, ws, res, q):
 
 
 def c2f_offered(x):
-    """The coarse-to-fine sweep exists only where the tile search runs it (fp32 up to 2^21 elements, bf16 below 2^20)."""
-    return x.size < (1 << 20) if x.dtype == np.uint16 else x.size <= (1 << 21)
+    """The coarse-to-fine sweep runs on the tile search for any fp32 tensor; bf16 tensors of 2^20 elements or more go
+    through their value table, where it is not offered."""
+    return x.size < (1 << 20) if x.dtype == np.uint16 else True
 
 
 @pytest.mark.parametrize("name,n", VARIANT_INPUTS, ids=[f"{c[0]}_{c[1]}" for c in VARIANT_INPUTS])
@@ -992,27 +993,43 @@ def test_clip_to_data_lowers_the_error_of_one_sided_data(qp):
         assert r1.mse_star < 0.85 * r0.mse_star and q1.lo == np.float32(st.min)
 
 
-def test_coarse_to_fine_is_refused_on_large_tensors(qp):
-    """Above the tile search's limit the coarse-to-fine sweep is switched off (it returns an error before
-    anything is launched); the full sweep with the same other settings still runs."""
-    for name, n in (("C3", 2_600_011), ("C5", 1_300_001)):
-        x = si.make_config(name, n=n)
-        xd = to_dev(x)
-        ws = qp.alloc_workspace(x.size)
-        st = qp.qp_stats(xd, ws)
-        with pytest.raises(qp.QuantPipeError) as e:
-            qp.qp_dsaciq_search(xd, st, 4, ws, cfg=variant_cfg(qp, dict(stride=10)))
-        assert e.value.status == qp.QP_EINVAL
-        packed = qp.alloc_packed(x.size, 4)
-        with pytest.raises(qp.QuantPipeError):
-            qp.qp_compress_async(xd, 4, ws, packed, cfg=variant_cfg(qp, dict(stride=10, clip=True)))
-        res, q = qp.qp_dsaciq_search(xd, st, 4, ws, cfg=variant_cfg(qp, dict(clip=True)))
-        check_variant(qp, as_f32(x), st, 4, dict(clip=True), 100, ws, res, q)
+def test_coarse_to_fine_is_refused_on_large_bf16_tensors(qp):
+    """bf16 tensors that go through their value table: the coarse-to-fine sweep returns an error before anything is
+    launched; the full sweep with the same other settings still runs."""
+    x = si.make_config("C5", n=1_300_001)
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    with pytest.raises(qp.QuantPipeError) as e:
+        qp.qp_dsaciq_search(xd, st, 4, ws, cfg=variant_cfg(qp, dict(stride=10)))
+    assert e.value.status == qp.QP_EINVAL
+    packed = qp.alloc_packed(x.size, 4)
+    with pytest.raises(qp.QuantPipeError):
+        qp.qp_compress_async(xd, 4, ws, packed, cfg=variant_cfg(qp, dict(stride=10, clip=True)))
+    res, q = qp.qp_dsaciq_search(xd, st, 4, ws, cfg=variant_cfg(qp, dict(clip=True)))
+    check_variant(qp, as_f32(x), st, 4, dict(clip=True), 100, ws, res, q)
 
 
-@pytest.mark.skip(reason="the coarse-to-fine sweep on the streaming search kernel (fp32 tensors above 2^21 elements) faulted the "
-                         "GPU once; a CPU emulation of the same launch under ASan/UBSan is clean and the cause has not been "
-                         "found, so the library refuses this case and it must not run on a GPU until a cause is shown")
+@pytest.mark.timeout(900)
+def test_coarse_to_fine_on_the_full_vit_base_tensor(qp):
+    """C2 at full size (9.7 M elements): the sweep runs on the tile search (29 evaluations instead of 101) and finds
+    what its oracle finds; on this input that is also the full sweep's winner."""
+    x = si.make_config("C2")
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(x.size)
+    st = qp.qp_stats(xd, ws)
+    for bits in (2, 4):
+        print(f"[case] coarse-to-fine C2 full bits={bits}", flush=True)
+        full, qf = qp.qp_dsaciq_search(xd, st, bits, ws)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=variant_cfg(qp, dict(stride=10)))
+        check_variant(qp, x, st, bits, dict(stride=10), 100, ws, res, q)
+        assert res.j_star == full.j_star and bytes(q) == bytes(qf)
+
+
+@pytest.mark.skip(reason="the coarse-to-fine sweep on the STREAMING search kernel (k_search_mse with a coarse / fine candidate "
+                         "list) faulted the GPU once; a CPU emulation of the same launch under ASan/UBSan is clean and the "
+                         "cause has not been found, so the library never launches that kernel with such a list (the sweep "
+                         "runs on the tile search instead) and the case must not run on a GPU until a cause is shown")
 def test_coarse_to_fine_on_the_streaming_kernel(qp):
     x = si.make_config("C3", n=2_600_011)
     xd = to_dev(x)

@@ -227,14 +227,15 @@ def test_make_qparams_clipped_is_bit_identical_to_the_oracle(qp):
         qp.qp_make_qparams_clipped(0.0, 1.0, -1.0, 1.0, 5, 1)
 
 
-def test_coarse_to_fine_is_refused_where_it_is_switched_off(qp):
-    """fp32 above 2^21 elements and bf16 from 2^20: QP_EINVAL before anything is launched (no GPU needed)."""
+def test_coarse_to_fine_is_refused_where_it_is_not_offered(qp):
+    """bf16 tensors of 2^20 elements or more (searched through their value table): QP_EINVAL before anything is
+    launched (no GPU needed)."""
     L = qp.lib()
     fake, big = C.c_void_p(0x1000), 1 << 40
     st, res, qo = qp.qp_stats_t(), qp.qp_search_result_t(), qp.qp_qparams_t()
     cfg = qp.qp_default_search_cfg()
     cfg.flags, cfg.coarse_stride = qp.QP_SEARCH_COARSE_TO_FINE, 10
-    for n, dtype in ((3_000_000, qp.QP_F32), ((1 << 21) + 1, qp.QP_F32), (1 << 20, qp.QP_BF16), (200_000_000, qp.QP_BF16)):
-        assert L.qp_dsaciq_search(fake, n, dtype, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
-        assert L.qp_dsaciq_search_async(fake, n, dtype, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
-        assert L.qp_compress_async(fake, n, dtype, 4, C.byref(cfg), fake, big, fake, big, None, None) == qp.QP_EINVAL
+    for n in (1 << 20, 200_000_000):
+        assert L.qp_dsaciq_search(fake, n, qp.QP_BF16, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
+        assert L.qp_dsaciq_search_async(fake, n, qp.QP_BF16, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
+        assert L.qp_compress_async(fake, n, qp.QP_BF16, 4, C.byref(cfg), fake, big, fake, big, None, None) == qp.QP_EINVAL

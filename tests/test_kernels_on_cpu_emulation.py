@@ -109,8 +109,10 @@ TILE_CASES = [("C1", 3_011, 2, {}, 100), ("C3", 4_999, 3, {}, 12), ("bf16", 5_34
               ("bf16", 2_777, 8, dict(stride=3, clip=True), 12), ("C1", 5, 4, {}, 5), ("C3", 1, 8, {}, 3)]
 # the same kind of tensors through the kernels large tensors take (thresholds lowered at build time)
 STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37), ("bf16", 5_001, 4, {}, 30),
-                ("bf16", 3_000, 3, dict(dist=1), 20), ("C1", 2_049, 6, {}, 1)]
-REFUSED = ("C3", 5_000, 4, dict(stride=10), 100)
+                ("bf16", 3_000, 3, dict(dist=1), 20), ("C1", 2_049, 6, {}, 1),
+                # a coarse-to-fine sweep of a tensor above the tile search's size limit still runs on the tile search
+                ("C3", 9_001, 4, dict(stride=5), 40)]
+REFUSED = ("bf16", 5_000, 4, dict(stride=10), 100)
 ALL_CASES = [("default", c) for c in TILE_CASES] + [("streaming", c) for c in STREAM_CASES] + [("streaming", REFUSED)]
 
 
@@ -149,7 +151,7 @@ def test_whole_path_on_the_emulation(runs, tag, case):
 
 
 def test_emulation_refuses_what_the_library_refuses(runs):
-    """Coarse-to-fine is switched off outside the tile search: the search returns QP_EINVAL and nothing more runs."""
+    """Coarse-to-fine is not offered for bf16 tensors that go through their value table: QP_EINVAL, nothing more runs."""
     p, out_dir, x = runs[case_id("streaming", REFUSED)]
     r = read_outputs(p, out_dir)
     assert r["rc"][0] == 0 and r["rc"][1] == -1
