@@ -198,8 +198,12 @@ bool tile_search_eligible(uint64_t n, const SearchPlan &plan)
 
 static uint64_t tile_share(uint64_t n)
 {
-    // shares of whole 128-element groups, at least 512 elements, at most kStMaxBlocks of them
-    uint64_t share = (n + kStMaxBlocks - 1) / kStMaxBlocks;
+    // Shares of whole 128-element groups, at least 512 elements.  The grid is a whole number of blocks per
+    // compute unit (no unit gets one more than another): one, or two from about two sub-tiles per unit on,
+    // whose staging and scoring then overlap (2 M elements: 62 -> 57 us; coarse-to-fine on 9.7 M: 103 -> 90 us).
+    const uint64_t per_cu = (n + (uint64_t)kStMaxBlocks * kStSub / 2) / ((uint64_t)kStMaxBlocks * kStSub);   // rounded
+    const uint64_t blocks = (uint64_t)kStMaxBlocks * (per_cu >= 2 ? 2 : 1);
+    uint64_t share = (n + blocks - 1) / blocks;
     share = (share + 127) / 128 * 128;
     return share < 512 ? 512 : share;
 }
