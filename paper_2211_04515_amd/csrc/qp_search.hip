@@ -1,4 +1,6 @@
-// Step 2b: DS-ACIQ directed search (Sec. 3, Eq. 1).
+// Step 2b: DS-ACIQ directed search (Sec. 3, Eq. 1): the streaming kernel for large tensors (above
+// 2^21 elements; smaller ones, and every coarse-to-fine sweep, take the tile search in
+// qp_search_tile.hip; large bf16 tensors are searched here through their value table).
 //
 // t+1 candidate scales b_j = b_E + j (b_R - b_E)/t walk from the ACIQ estimate towards the
 // bound given by the real histogram's peak.  Each candidate is scored by the squared
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(kFinThreads) void k_search_setup(ModelArgs m, qp_st
 
 // The scoring pass of one block: lanes stride over batches of kSrElems elements; for each
 // batch the round's candidates (at most 32, wave-uniform) are applied to the elements held in
-// registers.  SHORT selects the sequence without the second clamp (see k_search_setup).
+// registers.  SHORT selects the sequence without the second clamp (see setup_candidates).
 template <int DT, int CMAX, bool SHORT>
 __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t n, const Cand *sh_cands, uint32_t nc,
                                            float Lf, double (&acc)[CMAX])

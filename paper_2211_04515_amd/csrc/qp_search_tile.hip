@@ -94,7 +94,7 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
     const uint32_t slice = tid / ncand, c = tid - slice * ncand;
     const bool active = slice < S;
     const Cand p = sh_cands[active ? c : 0u];
-    double acc = 0.0;
+    double acc0 = 0.0, acc1 = 0.0;
     for (uint64_t e0 = e_begin; e0 < e_end; e0 += kStSub) {
         __syncthreads();   // the previous sub-tile has been read
 #pragma unroll
@@ -109,7 +109,7 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
             const uint32_t g0 = min(slice * per, nv4), g1 = min(g0 + per, nv4);
             auto run = [&](auto short_tag) {
                 constexpr bool SHORT = decltype(short_tag)::value;
-                auto one = [&](float xv) {
+                auto one = [&](float xv, double &acc) {
                     float r;
                     if constexpr (SHORT) {
                         // med3(x, lo, hi) == min(max(x, lo), hi) for lo <= hi, NaN -> lo as well
@@ -124,21 +124,36 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
                     const double de = (double)err;
                     acc = fma(de, de, acc);   // de*de is exact in fp64
                 };
-                for (uint32_t g = g0; g < g1; ++g) {
-                    const float4 xv = reinterpret_cast<const float4 *>(sh_x)[g];
-                    one(xv.x);
-                    one(xv.y);
-                    one(xv.z);
-                    one(xv.w);
+                // two groups of four per step, each with its own running sum: both LDS reads are issued
+                // before the arithmetic, and the two fp64 accumulation chains interleave
+                uint32_t g = g0;
+                for (; g + 2 <= g1; g += 2) {
+                    const float4 xa = reinterpret_cast<const float4 *>(sh_x)[g];
+                    const float4 xb = reinterpret_cast<const float4 *>(sh_x)[g + 1];
+                    one(xa.x, acc0);
+                    one(xb.x, acc1);
+                    one(xa.y, acc0);
+                    one(xb.y, acc1);
+                    one(xa.z, acc0);
+                    one(xb.z, acc1);
+                    one(xa.w, acc0);
+                    one(xb.w, acc1);
+                }
+                if (g < g1) {
+                    const float4 xa = reinterpret_cast<const float4 *>(sh_x)[g];
+                    one(xa.x, acc0);
+                    one(xa.y, acc0);
+                    one(xa.z, acc0);
+                    one(xa.w, acc0);
                 }
                 if (slice == 0)   // the tensor's ragged end (fewer than 4 elements)
-                    for (uint32_t e = 4u * nv4; e < nv; ++e) one(sh_x[e]);
+                    for (uint32_t e = 4u * nv4; e < nv; ++e) one(sh_x[e], acc0);
             };
             if (safe) run(std::true_type{});
             else run(std::false_type{});
         }
     }
-    if (active) sh_acc[tid] = acc;
+    if (active) sh_acc[tid] = acc0 + acc1;
     __syncthreads();
     if (tid < ncand) {
         double s = sh_acc[tid];
