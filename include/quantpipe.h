@@ -242,7 +242,10 @@ qp_status qp_unpack_dequant_dev(const void *packed_dev, size_t packed_bytes, uin
 /* ---- whole sender side without a host round trip ------------------------------
  * stats -> directed search -> quantize + pack, all on `stream`, nothing copied to the
  * host.  If qparams_out_dev is not NULL the winner's record is also copied there
- * (device to device) so that it can travel with the payload. */
+ * (device to device) so that it can travel with the payload.  The statistics, the
+ * search result and the scores are left in the workspace regions as by the separate
+ * calls; nothing is reported about NaN / Inf elements here (QP_WS_STATS holds their
+ * count; such elements are packed as code 0). */
 qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
                             const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
                             void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev,
