@@ -566,3 +566,56 @@ int orc_dsaciq_search_variant(const float *x, uint64_t n, const orc_stats_t *st,
     }
     return 0;
 }
+
+/* ---- Adaptive PDA controller: window averages feeding Eq. 2 (Sec. 3 "Adaptive PDA", Sec. 4.2) ----
+ * The runtime measures over a window of microbatches (50 in the paper's run) and decides when the
+ * window expires, from the window's averages: the bandwidth is what the link carried in the window,
+ * B = (sum of payload bits) / (sum of sending times), and V is the window's mean payload per
+ * microbatch at the current bitwidth.  Between expiries the bitwidth stays as it is. */
+typedef struct {
+    uint32_t window;       /* microbatches per decision */
+    uint32_t count;        /* microbatches seen in the current window */
+    double bits_sum;       /* payload bits sent in the current window */
+    double seconds_sum;    /* time the link took for them */
+    double s_images;       /* S: images per microbatch */
+    double r_rate;         /* R: target images per second */
+    uint32_t q_cur;        /* bitwidth in force (32 = unquantized) */
+    uint32_t decisions;    /* windows that have expired */
+} orc_controller_t;
+
+int orc_controller_init(orc_controller_t *c, uint32_t window, double s_images, double r_rate, uint32_t q_start)
+{
+    if (!c || window == 0 || !(s_images > 0.0) || !(r_rate > 0.0) || q_start == 0) return 2;
+    c->window = window;
+    c->count = 0;
+    c->bits_sum = 0.0;
+    c->seconds_sum = 0.0;
+    c->s_images = s_images;
+    c->r_rate = r_rate;
+    c->q_cur = q_start;
+    c->decisions = 0;
+    return 0;
+}
+
+/* one microbatch has been sent; *q_next is the bitwidth for the next one */
+int orc_controller_update(orc_controller_t *c, double payload_bits, double seconds, uint32_t *q_next)
+{
+    if (!c || !q_next || !(payload_bits > 0.0) || !(seconds > 0.0)) return 2;
+    c->bits_sum += payload_bits;
+    c->seconds_sum += seconds;
+    c->count += 1;
+    if (c->count == c->window) {
+        double bandwidth = c->bits_sum / c->seconds_sum;
+        double v_mean = c->bits_sum / (double)c->window;
+        uint32_t q;
+        int rc = orc_next_bits(v_mean, c->q_cur, c->s_images, c->r_rate, bandwidth, &q);
+        if (rc) return rc;
+        c->q_cur = q;
+        c->count = 0;
+        c->bits_sum = 0.0;
+        c->seconds_sum = 0.0;
+        c->decisions += 1;
+    }
+    *q_next = c->q_cur;
+    return 0;
+}

@@ -42,6 +42,11 @@ class SearchResult(C.Structure):
 _lib = None
 
 
+class Controller(C.Structure):
+    _fields_ = [("window", C.c_uint32), ("count", C.c_uint32), ("bits_sum", C.c_double), ("seconds_sum", C.c_double),
+                ("s_images", C.c_double), ("r_rate", C.c_double), ("q_cur", C.c_uint32), ("decisions", C.c_uint32)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -89,6 +94,10 @@ def lib():
         L.orc_hist_search.restype = C.c_int
         L.orc_next_bits.argtypes = [C.c_double, C.c_uint32, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_uint32)]
         L.orc_next_bits.restype = C.c_int
+        L.orc_controller_init.argtypes = [C.POINTER(Controller), C.c_uint32, C.c_double, C.c_double, C.c_uint32]
+        L.orc_controller_init.restype = C.c_int
+        L.orc_controller_update.argtypes = [C.POINTER(Controller), C.c_double, C.c_double, C.POINTER(C.c_uint32)]
+        L.orc_controller_update.restype = C.c_int
         L.orc_make_qparams_clipped.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint32, C.c_uint64,
                                                C.POINTER(QParams)]
         L.orc_make_qparams_clipped.restype = C.c_int
@@ -275,3 +284,19 @@ def dsaciq_search_variant(x, st, bits, t_steps=100, dist=LAPLACE, clip_to_data=F
     if rc:
         raise ValueError("orc_dsaciq_search_variant: bad argument")
     return res, q, scores
+
+
+# ---- adaptive PDA controller (window averages feeding Eq. 2) --------------------------------------
+
+def controller(window, s_images, r_rate, q_start=32):
+    c = Controller()
+    if lib().orc_controller_init(C.byref(c), int(window), float(s_images), float(r_rate), int(q_start)):
+        raise ValueError("orc_controller_init: bad argument")
+    return c
+
+
+def controller_update(c, payload_bits, seconds):
+    q = C.c_uint32()
+    if lib().orc_controller_update(C.byref(c), float(payload_bits), float(seconds), C.byref(q)):
+        raise ValueError("orc_controller_update: bad argument")
+    return q.value

@@ -677,3 +677,76 @@ def test_coarse_to_fine_search_equals_pick_on_the_full_sweep():
                 assert bytes(q) == bytes(full_q) and r.alpha_star == full_r.alpha_star
         # on these inputs the sweep with stride 10 does find the full sweep's winner
         assert orc.c2f_pick(full, 10)[0] == full_r.j_star
+
+
+# ----------------------------------------------------------------------------- adaptive PDA controller (Sec. 3, Sec. 4.2)
+
+def _replay_link(update, bandwidths_mbps, per_phase, n_elems, latency_s=0.0):
+    """Send microbatches over a link whose bandwidth changes per phase (the controller is not told); the
+    time a microbatch takes is its payload divided by the bandwidth in force.  Returns the bitwidth used
+    for every microbatch."""
+    used = []
+    q = 32
+    for bw in bandwidths_mbps:
+        for _ in range(per_phase):
+            used.append(q)
+            bits = n_elems * q
+            seconds = bits / (bw * 1e6) + latency_s if np.isfinite(bw) else 1e-6
+            q = update(bits, seconds)
+    return used
+
+
+def test_controller_reproduces_the_papers_five_phases():
+    """Sec. 4.2: window 50, microbatch 64, about 100 images/s; bandwidth unlimited -> 400 -> 50 -> 200 -> unlimited
+    Mbps at 200-microbatch intervals; the bitwidth settles at 32 -> 16 -> 2 -> 8 -> 32, each one window period after
+    the change."""
+    n = 64 * 197 * 768
+    c = orc.controller(50, 64, 100.0)
+    used = _replay_link(lambda b, s: orc.controller_update(c, b, s), [np.inf, 400, 50, 200, np.inf], 200, n)
+    settled = [used[200 * p + 199] for p in range(5)]
+    assert settled == [32] + [q for _, q in _golden_adaptive()]
+    for p in range(1, 5):
+        phase = used[200 * p:200 * (p + 1)]
+        assert phase[:50] == [settled[p - 1]] * 50           # nothing changes before the window expires
+        assert phase[50:] == [settled[p]] * 150              # one decision, then stable
+    assert c.decisions == 20
+
+
+def test_controller_change_inside_a_window_gives_one_transient_decision():
+    """When the bandwidth changes in the middle of a window the window average is a mixture, so one intermediate
+    bitwidth may be chosen before the next window settles (the paper's run shows such a transient in phase 3)."""
+    n = 64 * 197 * 768
+    c = orc.controller(50, 64, 100.0, q_start=2)
+    used = []
+    q = 2
+    for m in range(400):
+        bw = 50e6 if m < 125 else 200e6          # change half-way through the third window
+        used.append(q)
+        q = orc.controller_update(c, n * q, n * q / bw)
+    assert used[:150] == [2] * 150
+    assert set(used[150:200]) == {4}              # the mixed window: 2 bit payloads at 50 and 200 Mbps average 80 Mbps
+    assert used[200:] == [8] * 200
+
+
+def test_controller_decides_exactly_what_eq2_decides_on_the_window_averages():
+    rng = np.random.default_rng(8)
+    for trial in range(50):
+        window = int(rng.integers(1, 20))
+        s_img, rate = float(rng.integers(1, 65)), float(rng.uniform(10, 300))
+        c = orc.controller(window, s_img, rate, q_start=int(rng.choice([32, 16, 8, 4, 2])))
+        n = int(rng.integers(100_000, 20_000_000))
+        q = c.q_cur
+        bits_w, secs_w = [], []
+        for m in range(window * 6):
+            bits = n * q
+            secs = bits / float(10 ** rng.uniform(6.5, 9.5))
+            bits_w.append(bits)
+            secs_w.append(secs)
+            q_new = orc.controller_update(c, bits, secs)
+            if (m + 1) % window == 0:
+                expect = orc.next_bits(sum(bits_w) / window, q, s_img, rate, sum(bits_w) / sum(secs_w))
+                assert q_new == expect
+                bits_w, secs_w = [], []
+            else:
+                assert q_new == q
+            q = q_new
