@@ -263,6 +263,31 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
 qp_status qp_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_images_per_s,
                        double bandwidth_bits_per_s, uint32_t *q_next);
 
+/* ---- adaptive PDA controller: window averages feeding Eq. 2 (Sec. 3, Sec. 4.2) -- host only ----
+ * The paper's runtime measures over a window of microbatches (50 in its run) and decides when the
+ * window expires, from the window's averages.  The caller reports every microbatch it has sent
+ * (payload bits at the bitwidth in force, and the time the link took); when `window` of them have
+ * been reported the bandwidth B = sum(bits) / sum(seconds) and the mean payload V go into
+ * qp_next_bits, and its answer is the bitwidth from then on.  Between expiries nothing changes.
+ * The record is plain data owned by the caller (one per stage boundary); no allocation. */
+typedef struct {
+    uint32_t window;           /* microbatches per decision */
+    uint32_t count;            /* microbatches reported in the current window */
+    double   bits_sum;         /* payload bits in the current window */
+    double   seconds_sum;      /* time the link took for them */
+    double   s_images;         /* S: images per microbatch */
+    double   r_images_per_s;   /* R: target rate */
+    uint32_t q_cur;            /* bitwidth in force: 2,3,4,6,8,16, or 32 = send unquantized */
+    uint32_t decisions;        /* windows that have expired */
+} qp_controller_t;
+
+/* QP_EINVAL on window == 0, non-positive S or R, or a q_start that is not a bitwidth or 32. */
+qp_status qp_controller_init(qp_controller_t *c, uint32_t window, double s_images, double r_images_per_s,
+                             uint32_t q_start);
+/* One microbatch has been sent; *q_next receives the bitwidth for the next one.
+ * QP_EINVAL on null pointers or non-positive / NaN payload_bits or seconds (the record is unchanged). */
+qp_status qp_controller_update(qp_controller_t *c, double payload_bits, double seconds, uint32_t *q_next);
+
 const char *qp_strerror(qp_status status);
 
 #ifdef __cplusplus

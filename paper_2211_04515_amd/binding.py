@@ -15,11 +15,11 @@ __all__ = [
     "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS",
     "QP_SEARCH_CLIP_TO_DATA", "QP_SEARCH_COARSE_TO_FINE",
     "QP_WS_STATS", "QP_WS_RESULT", "QP_WS_QPARAMS", "QP_WS_HIST", "QP_WS_CANDS", "QP_WS_SCORES",
-    "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "QuantPipeError", "BITS",
+    "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "qp_controller_t", "QuantPipeError", "BITS",
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
     "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
     "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
-    "qp_compress_async", "qp_next_bits", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
+    "qp_compress_async", "qp_next_bits", "qp_controller_init", "qp_controller_update", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
 ]
 
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
@@ -47,6 +47,11 @@ class qp_qparams_t(C.Structure):
 class qp_search_cfg_t(C.Structure):
     _fields_ = [("t_steps", C.c_uint32), ("cands_per_round", C.c_uint32), ("nbins", C.c_uint32),
                 ("dist", C.c_uint32), ("flags", C.c_uint32), ("coarse_stride", C.c_uint32)]
+
+
+class qp_controller_t(C.Structure):
+    _fields_ = [("window", C.c_uint32), ("count", C.c_uint32), ("bits_sum", C.c_double), ("seconds_sum", C.c_double),
+                ("s_images", C.c_double), ("r_images_per_s", C.c_double), ("q_cur", C.c_uint32), ("decisions", C.c_uint32)]
 
 
 class qp_search_result_t(C.Structure):
@@ -97,6 +102,8 @@ def lib():
             "qp_unpack_dequant_dev": (i32, [vp, sz, u32, vp, vp, u64, vp]),
             "qp_compress_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, sz, vp, vp]),
             "qp_next_bits": (i32, [C.c_double, u32, C.c_double, C.c_double, C.c_double, C.POINTER(u32)]),
+            "qp_controller_init": (i32, [C.POINTER(qp_controller_t), u32, C.c_double, C.c_double, u32]),
+            "qp_controller_update": (i32, [C.POINTER(qp_controller_t), C.c_double, C.c_double, C.POINTER(u32)]),
             "qp_strerror": (C.c_char_p, [i32]),
         }
         for name, (res, args) in sig.items():
@@ -110,7 +117,8 @@ def lib():
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
            "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
            "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
-           "qp_unpack_dequant_dev", "qp_compress_async", "qp_next_bits", "qp_strerror")
+           "qp_unpack_dequant_dev", "qp_compress_async", "qp_next_bits", "qp_controller_init", "qp_controller_update",
+           "qp_strerror")
 
 
 # ---- marshalling helpers ------------------------------------------------------------------
@@ -275,6 +283,19 @@ def qp_next_bits(v_bits: float, q_cur: int, s_images: float, r_images_per_s: flo
     out = C.c_uint32()
     _check(lib().qp_next_bits(float(v_bits), int(q_cur), float(s_images), float(r_images_per_s),
                               float(bandwidth_bits_per_s), C.byref(out)), "qp_next_bits")
+    return out.value
+
+
+def qp_controller_init(window: int, s_images: float, r_images_per_s: float, q_start: int = 32) -> qp_controller_t:
+    c = qp_controller_t()
+    _check(lib().qp_controller_init(C.byref(c), int(window), float(s_images), float(r_images_per_s), int(q_start)),
+           "qp_controller_init")
+    return c
+
+
+def qp_controller_update(c: qp_controller_t, payload_bits: float, seconds: float) -> int:
+    out = C.c_uint32()
+    _check(lib().qp_controller_update(C.byref(c), float(payload_bits), float(seconds), C.byref(out)), "qp_controller_update")
     return out.value
 
 

@@ -364,6 +364,46 @@ qp_status qp_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_
     return QP_OK;
 }
 
+qp_status qp_controller_init(qp_controller_t *c, uint32_t window, double s_images, double r_images_per_s,
+                             uint32_t q_start)
+{
+    if (!c || window == 0 || !(s_images > 0.0) || !(r_images_per_s > 0.0) || std::isinf(s_images) ||
+        std::isinf(r_images_per_s) || !(bits_ok(q_start) || q_start == 32))
+        return QP_EINVAL;
+    c->window = window;
+    c->count = 0;
+    c->bits_sum = 0.0;
+    c->seconds_sum = 0.0;
+    c->s_images = s_images;
+    c->r_images_per_s = r_images_per_s;
+    c->q_cur = q_start;
+    c->decisions = 0;
+    return QP_OK;
+}
+
+qp_status qp_controller_update(qp_controller_t *c, double payload_bits, double seconds, uint32_t *q_next)
+{
+    if (!c || !q_next || !(payload_bits > 0.0) || !(seconds > 0.0) || std::isinf(payload_bits) || std::isinf(seconds))
+        return QP_EINVAL;
+    if (c->count + 1 == c->window) {   // this report closes the window: decide on its averages
+        const double bits = c->bits_sum + payload_bits, secs = c->seconds_sum + seconds;
+        uint32_t q = c->q_cur;
+        const qp_status st = qp_next_bits(bits / (double)c->window, c->q_cur, c->s_images, c->r_images_per_s, bits / secs, &q);
+        if (st != QP_OK) return st;
+        c->q_cur = q;
+        c->count = 0;
+        c->bits_sum = 0.0;
+        c->seconds_sum = 0.0;
+        c->decisions += 1;
+    } else {
+        c->bits_sum += payload_bits;
+        c->seconds_sum += seconds;
+        c->count += 1;
+    }
+    *q_next = c->q_cur;
+    return QP_OK;
+}
+
 const char *qp_strerror(qp_status status)
 {
     switch (status) {

@@ -239,3 +239,41 @@ def test_coarse_to_fine_is_refused_where_it_is_not_offered(qp):
         assert L.qp_dsaciq_search(fake, n, qp.QP_BF16, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
         assert L.qp_dsaciq_search_async(fake, n, qp.QP_BF16, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
         assert L.qp_compress_async(fake, n, qp.QP_BF16, 4, C.byref(cfg), fake, big, fake, big, None, None) == qp.QP_EINVAL
+
+
+def test_controller_is_the_oracles_controller(qp):
+    """qp_controller_* against the oracle on random traces (same decision after every microbatch) and on the paper's
+    five-phase run (Sec. 4.2)."""
+    assert C.sizeof(qp.qp_controller_t) == 48
+    rng = np.random.default_rng(21)
+    for trial in range(40):
+        window = int(rng.integers(1, 30))
+        s_img, rate = float(rng.integers(1, 65)), float(rng.uniform(10, 300))
+        q0 = int(rng.choice([32, 16, 8, 6, 4, 3, 2]))
+        a, b = qp.qp_controller_init(window, s_img, rate, q0), orc.controller(window, s_img, rate, q0)
+        n = int(rng.integers(100_000, 20_000_000))
+        q = q0
+        for m in range(window * 5 + 3):
+            bits = float(n * q)
+            secs = bits / float(10 ** rng.uniform(6.5, 9.5))
+            qa, qb = qp.qp_controller_update(a, bits, secs), orc.controller_update(b, bits, secs)
+            assert qa == qb and (a.count, a.decisions, a.q_cur) == (b.count, b.decisions, b.q_cur)
+            q = qa
+    n = 64 * 197 * 768
+    c = qp.qp_controller_init(50, 64, 100.0)
+    used, q = [], 32
+    for bw in (np.inf, 400e6, 50e6, 200e6, np.inf):
+        for _ in range(200):
+            used.append(q)
+            q = qp.qp_controller_update(c, n * q, n * q / bw if np.isfinite(bw) else 1e-6)
+    assert [used[200 * p + 199] for p in range(5)] == [32, 16, 2, 8, 32]
+    L = qp.lib()
+    out = C.c_uint32()
+    assert L.qp_controller_init(None, 50, 64.0, 100.0, 32) == qp.QP_EINVAL
+    for args in ((0, 64.0, 100.0, 32), (50, 0.0, 100.0, 32), (50, 64.0, -1.0, 32), (50, 64.0, 100.0, 5), (50, float("nan"), 100.0, 32)):
+        assert L.qp_controller_init(C.byref(c), *args) == qp.QP_EINVAL, args
+    c = qp.qp_controller_init(2, 64, 100.0)
+    for bits, secs in ((0.0, 1.0), (1.0, 0.0), (float("nan"), 1.0), (1.0, float("inf"))):
+        assert L.qp_controller_update(C.byref(c), bits, secs, C.byref(out)) == qp.QP_EINVAL
+    assert (c.count, c.decisions) == (0, 0)
+    assert L.qp_controller_update(C.byref(c), 1.0, 1.0, None) == qp.QP_EINVAL
