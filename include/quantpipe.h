@@ -104,9 +104,15 @@ typedef struct {
  *                               (0 = 10; at most 64).  Scores of candidates that were never
  *                               evaluated are NaN in QP_WS_SCORES.  Not offered for bf16 tensors of
  *                               2^20 elements or more (QP_EINVAL): those are searched through the
- *                               table of their 65536 possible values, where the full sweep is cheap. */
+ *                               table of their 65536 possible values, where the full sweep is cheap.
+ *   QP_SEARCH_LOW_BITS_ONLY     the deployment policy the paper reports (Sec. 4.1: the directed search
+ *                               is only activated under 4- and 2-bit quantization, because above that
+ *                               it gains nothing): for bits > 4 no candidate is scored and the result
+ *                               is plain ACIQ (j_star = 0, alpha = F(q) b_E; mse_aciq, mse_star and
+ *                               QP_WS_SCORES are NaN); for bits <= 4 the search runs as configured. */
 #define QP_SEARCH_CLIP_TO_DATA 1u
 #define QP_SEARCH_COARSE_TO_FINE 2u
+#define QP_SEARCH_LOW_BITS_ONLY 4u
 typedef struct {
     uint32_t t_steps;          /* 1..1023: candidates j = 0..t_steps */
     uint32_t cands_per_round;  /* 1..32: most candidates scored per pass over the tensor (small tensors use

@@ -13,7 +13,7 @@ import torch  # noqa: F401  (must precede CDLL: one HIP runtime per process)
 
 __all__ = [
     "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS",
-    "QP_SEARCH_CLIP_TO_DATA", "QP_SEARCH_COARSE_TO_FINE",
+    "QP_SEARCH_CLIP_TO_DATA", "QP_SEARCH_COARSE_TO_FINE", "QP_SEARCH_LOW_BITS_ONLY",
     "QP_WS_STATS", "QP_WS_RESULT", "QP_WS_QPARAMS", "QP_WS_HIST", "QP_WS_CANDS", "QP_WS_SCORES",
     "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "qp_controller_t", "QuantPipeError", "BITS",
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
@@ -25,7 +25,7 @@ __all__ = [
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
 QP_F32, QP_BF16 = 0, 1
 QP_LAPLACE, QP_GAUSS = 0, 1
-QP_SEARCH_CLIP_TO_DATA, QP_SEARCH_COARSE_TO_FINE = 1, 2
+QP_SEARCH_CLIP_TO_DATA, QP_SEARCH_COARSE_TO_FINE, QP_SEARCH_LOW_BITS_ONLY = 1, 2, 4
 QP_WS_STATS, QP_WS_RESULT, QP_WS_QPARAMS, QP_WS_HIST, QP_WS_CANDS, QP_WS_SCORES = range(6)
 BITS = (2, 3, 4, 6, 8, 16)
 

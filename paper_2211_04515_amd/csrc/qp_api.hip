@@ -66,7 +66,7 @@ qp_status check_cfg(const qp_search_cfg_t *cfg)
     if (cfg->t_steps < 1 || cfg->t_steps > kMaxT) return QP_EINVAL;
     if (cfg->cands_per_round < 1 || cfg->cands_per_round > kMaxCandsPerRound) return QP_EINVAL;
     if (cfg->dist != QP_LAPLACE && cfg->dist != QP_GAUSS) return QP_EINVAL;
-    if (cfg->flags & ~(QP_SEARCH_CLIP_TO_DATA | QP_SEARCH_COARSE_TO_FINE)) return QP_EINVAL;
+    if (cfg->flags & ~(QP_SEARCH_CLIP_TO_DATA | QP_SEARCH_COARSE_TO_FINE | QP_SEARCH_LOW_BITS_ONLY)) return QP_EINVAL;
     if (cfg->coarse_stride > 64u) return QP_EINVAL;
     return QP_OK;
 }
@@ -83,6 +83,7 @@ SearchPlan make_plan(uint32_t bits, const qp_search_cfg_t *cfg)
     p.clip = (cfg && (cfg->flags & QP_SEARCH_CLIP_TO_DATA)) ? 1u : 0u;
     p.stride = 1u;
     if (cfg && (cfg->flags & QP_SEARCH_COARSE_TO_FINE)) p.stride = cfg->coarse_stride ? cfg->coarse_stride : 10u;
+    p.aciq_only = (cfg && (cfg->flags & QP_SEARCH_LOW_BITS_ONLY) && bits > 4u) ? 1u : 0u;
     return p;
 }
 
@@ -206,7 +207,7 @@ static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, co
     const qp_status w = check_ws(n, cfg, ws_dev, ws_bytes);
     if (w != QP_OK) return w;
     const SearchPlan plan = make_plan(bits, cfg);
-    if (plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;   // see quantpipe.h
+    if (!plan.aciq_only && plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;   // see quantpipe.h
     return hip_status(launch_search(x_dev, n, dtype, plan, stats, finalize_nbins, value_table_ready, ws_dev,
                                     static_cast<hipStream_t>(stream)));
 }
@@ -325,7 +326,7 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     if (st != QP_OK) return st;
     {   // refuse what the search would refuse before anything is launched
         const SearchPlan plan = make_plan(bits, cfg);
-        if (plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;
+        if (!plan.aciq_only && plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;
     }
     // The two statistics passes leave partials and the search finalizes them itself; a large bf16 tensor goes
     // through its value table instead, which the statistics build and finalize and the search then reuses.

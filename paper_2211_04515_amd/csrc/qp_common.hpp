@@ -497,6 +497,7 @@ struct SearchPlan {
     uint32_t dist;       // QP_LAPLACE / QP_GAUSS
     uint32_t clip;       // intersect candidate ranges with the data's range
     uint32_t stride;     // 1: all t + 1 candidates; > 1: coarse sweep with this stride, then a fine one
+    uint32_t aciq_only;  // 1: score nothing, the result is plain ACIQ (j = 0)
 };
 
 // The two ends of the scale grid under a model: the moment estimate and the bound given by the

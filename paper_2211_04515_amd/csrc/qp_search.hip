@@ -50,6 +50,41 @@ __global__ __launch_bounds__(kFinThreads) void k_search_setup(ModelArgs m, qp_st
     setup_candidates(m, m.from_ws ? stats_dev : nullptr, j1, n, cands, nullptr, ctl, scores_by_j);
 }
 
+// No search: the result is plain ACIQ, candidate j = 0 (the paper's deployment switches the directed search
+// off above 4 bit).  One block; finalizes the statistics first when the sender path left partials.
+__global__ __launch_bounds__(kFinThreads) void k_aciq_only(ModelArgs m, qp_stats_t *__restrict__ stats_dev, uint64_t n,
+                                                           Cand *__restrict__ cands, Ctl *__restrict__ ctl, FinalizeArgs fin,
+                                                           double *__restrict__ scores_by_j,
+                                                           qp_search_result_t *__restrict__ res,
+                                                           qp_qparams_t *__restrict__ best)
+{
+    if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
+    m.list_mode = kListFull;
+    m.count = 1u;
+    setup_candidates(m, m.from_ws ? stats_dev : nullptr, 0u, n, cands, nullptr, ctl, nullptr);
+    const double nan = __longlong_as_double(0x7ff8000000000000ll);
+    for (uint32_t j = threadIdx.x; j <= m.t_steps; j += blockDim.x) scores_by_j[j] = nan;
+    __syncthreads();   // the control record written by lane 0 above
+    if (threadIdx.x == 0) {
+        qp_search_result_t r;
+        r.b_e = ctl->b_e;
+        r.b_r = ctl->b_r;
+        r.b_star = ctl->b_e;
+        r.alpha_star = ctl->F * ctl->b_e;
+        r.mse_aciq = nan;
+        r.mse_star = nan;
+        r.j_star = 0u;
+        r.t_steps = m.t_steps;
+        *res = r;
+        qp_qparams_t q;
+        q.bits = m.bits;
+        q.reserved = 0u;
+        q.n = n;
+        make_grid(ctl->mean, r.alpha_star, m.bits, q.lo, q.hi, q.scale, q.inv_scale, ctl->clip != 0u, ctl->clip_lo, ctl->clip_hi);
+        *best = q;
+    }
+}
+
 // The scoring pass of one block: lanes stride over batches of kSrElems elements; for each
 // batch the round's candidates (at most 32, wave-uniform) are applied to the elements held in
 // registers.  SHORT selects the sequence without the second clamp (see setup_candidates).
@@ -451,6 +486,18 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
 {
     // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
     // them once (one pass over the tensor) and run the candidates over the value table.
+    if (plan.aciq_only) {
+        char *w = static_cast<char *>(ws);
+        FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
+                         reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
+        if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
+        hipLaunchKernelGGL(k_aciq_only, dim3(1), dim3(kFinThreads), 0, s, model_args(plan, st, kListFull, 1u),
+                           reinterpret_cast<qp_stats_t *>(w + kOffStats), n, reinterpret_cast<Cand *>(w + kOffCands),
+                           reinterpret_cast<Ctl *>(w + kOffCtl), fin, reinterpret_cast<double *>(w + kOffScores),
+                           reinterpret_cast<qp_search_result_t *>(w + kOffResult),
+                           reinterpret_cast<qp_qparams_t *>(w + kOffQParams));
+        return hipGetLastError();
+    }
     const bool by_values = uses_value_table(n, dtype);
     // other small and medium tensors: one candidate per lane over LDS tiles
     if (!by_values && tile_search_eligible(n, plan)) return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);

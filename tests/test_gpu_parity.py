@@ -1037,3 +1037,43 @@ def test_coarse_to_fine_on_the_streaming_kernel(qp):
     st = qp.qp_stats(xd, ws)
     res, q = qp.qp_dsaciq_search(xd, st, 2, ws, cfg=variant_cfg(qp, dict(stride=10)))
     check_variant(qp, x, st, 2, dict(stride=10), 100, ws, res, q)
+
+
+def test_low_bits_only_policy(qp):
+    """QP_SEARCH_LOW_BITS_ONLY (the deployment policy the paper reports: the directed search is active at 2 and 4 bit
+    only): above 4 bit the result is plain ACIQ and nothing is scored; at 4 bit and below the search runs as usual."""
+    for name, n in (("C1", None), ("C3", 2_600_011), ("C5", 1_300_001)):
+        x = si.make_config(name, n=n)
+        xf = as_f32(x)
+        xd = to_dev(x)
+        n_ = x.size
+        cfg = qp.qp_default_search_cfg()
+        cfg.flags = qp.QP_SEARCH_LOW_BITS_ONLY
+        for bits in (16, 8, 6, 4, 2):
+            print(f"[case] low-bits-only {name} n={n_} bits={bits}", flush=True)
+            ws = qp.alloc_workspace(n_)
+            ws.fill_(0x2D)
+            packed = qp.alloc_packed(n_, bits)
+            qp.qp_compress_async(xd, bits, ws, packed, cfg=cfg)
+            torch.cuda.synchronize()
+            st = qp.read_ws(ws, qp.QP_WS_STATS, qp.qp_stats_t)
+            res = qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)
+            q = qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)
+            off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+            scores = ws[off:off + 8 * 101].cpu().numpy().view(np.float64)
+            if bits > 4:
+                alpha = orc.aciq_alpha(oracle_stats_from(st), bits)
+                oq = orc.make_qparams(st.mean, alpha, bits, n_)
+                assert res.j_star == 0 and res.t_steps == 100 and np.isnan(scores).all()
+                assert np.isnan(res.mse_aciq) and np.isnan(res.mse_star)
+                assert (res.b_e, res.b_r, res.b_star) == (st.mad, st.b_r, st.mad)
+                assert res.alpha_star == pytest.approx(alpha, rel=1e-15)
+                assert (q.bits, q.n, q.lo, q.hi, q.scale, q.inv_scale) == (bits, n_, oq.lo, oq.hi, oq.scale, oq.inv_scale)
+                assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(xf, oq), bits))
+                # the separate call gives the same record
+                st2 = qp.qp_stats(xd, ws)
+                res2, q2 = qp.qp_dsaciq_search(xd, st2, bits, ws, cfg=cfg)
+                assert bytes(q2) == bytes(q) and res2.j_star == 0 and res2.alpha_star == res.alpha_star
+            else:
+                check_variant(qp, xf, st, bits, {}, 100, ws, res, q)
+                assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(xf, oracle_q_from(q)), bits))

@@ -113,7 +113,8 @@ STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37
                 # a coarse-to-fine sweep of a tensor above the tile search's size limit still runs on the tile search
                 ("C3", 9_001, 4, dict(stride=5), 40)]
 REFUSED = ("bf16", 5_000, 4, dict(stride=10), 100)
-ALL_CASES = [("default", c) for c in TILE_CASES] + [("streaming", c) for c in STREAM_CASES] + [("streaming", REFUSED)]
+ACIQ_ONLY = [("default", ("C3", 3_003, 8, dict(low_bits_only=True), 100)), ("streaming", ("bf16", 6_001, 6, dict(low_bits_only=True, clip=True), 100))]
+ALL_CASES = [("default", c) for c in TILE_CASES] + [("streaming", c) for c in STREAM_CASES] + [("streaming", REFUSED)] + ACIQ_ONLY
 
 
 def case_id(tag, c):
@@ -129,7 +130,7 @@ def runs(drivers, tmp_path_factory):
     def go(item):
         tag, (kind, n, bits, v, t) = item
         x = small_input(kind, n)
-        flags = (1 if v.get("clip") else 0) | (2 if v.get("stride", 1) > 1 else 0)
+        flags = (1 if v.get("clip") else 0) | (2 if v.get("stride", 1) > 1 else 0) | (4 if v.get("low_bits_only") else 0)
         out_dir = os.path.join(base, case_id(tag, item[1]))
         p = start_driver(drivers[tag], out_dir, x, bits, t=t, dist=v.get("dist", 0), flags=flags,
                          stride=v.get("stride", 0) if flags & 2 else 0, cus=4 if tag == "default" else 2)
@@ -139,7 +140,10 @@ def runs(drivers, tmp_path_factory):
         return dict(ex.map(go, ALL_CASES))
 
 
-@pytest.mark.parametrize("tag,case", [a for a in ALL_CASES if a[1] is not REFUSED], ids=[case_id(*a) for a in ALL_CASES if a[1] is not REFUSED])
+WHOLE = [a for a in ALL_CASES if a[1] is not REFUSED and a not in ACIQ_ONLY]
+
+
+@pytest.mark.parametrize("tag,case", WHOLE, ids=[case_id(*a) for a in WHOLE])
 def test_whole_path_on_the_emulation(runs, tag, case):
     """Statistics, search (tile search with the default thresholds; streaming search with rounds and tickets and,
     for bf16 of at least 4096 elements, the value table with the lowered ones), quantize+pack, unpack+dequantize
@@ -155,3 +159,24 @@ def test_emulation_refuses_what_the_library_refuses(runs):
     p, out_dir, x = runs[case_id("streaming", REFUSED)]
     r = read_outputs(p, out_dir)
     assert r["rc"][0] == 0 and r["rc"][1] == -1
+
+
+@pytest.mark.parametrize("tag,case", ACIQ_ONLY, ids=[case_id(*a) for a in ACIQ_ONLY])
+def test_low_bits_only_policy_on_the_emulation(runs, tag, case):
+    """Above 4 bit with QP_SEARCH_LOW_BITS_ONLY nothing is scored: the result is plain ACIQ from the statistics."""
+    kind, n, bits, v, t = case
+    p, out_dir, x = runs[case_id(tag, case)]
+    r = read_outputs(p, out_dir)
+    xf = orc.widen_bf16(x) if x.dtype == np.uint16 else x
+    assert r["rc"] == [0, 0, 0, 0, 0, 1]
+    st, res, q = r["stats"], r["res"], r["q"]
+    ost = orc.Stats()
+    for name, _ in orc.Stats._fields_:
+        setattr(ost, name, getattr(st, name))
+    alpha = orc.aciq_alpha(ost, bits)
+    oq = orc.make_qparams_clipped(st.mean, alpha, st.min, st.max, bits, n) if v.get("clip") else orc.make_qparams(st.mean, alpha, bits, n)
+    assert res.j_star == 0 and np.isnan(r["scores"]).all() and np.isnan(res.mse_star)
+    assert res.alpha_star == pytest.approx(alpha, rel=1e-15)
+    assert (q.bits, q.n, q.lo, q.hi, q.scale, q.inv_scale) == (bits, n, oq.lo, oq.hi, oq.scale, oq.inv_scale)
+    codes = orc.quantize(xf, oq)
+    assert np.array_equal(r["packed"], orc.pack(codes, bits)) and np.array_equal(r["y"], orc.dequantize(codes, oq))
