@@ -133,7 +133,7 @@ def test_argument_errors_are_reported_before_any_gpu_work(qp):
     assert L.qp_dsaciq_search(fake, 1000, 0, None, 4, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
     assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 5, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
     assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, None, fake, 1000, None, C.byref(res), C.byref(qo)) == qp.QP_ENOSPC
-    for field, value in (("dist", 2), ("flags", 4), ("coarse_stride", 65), ("cands_per_round", 33), ("t_steps", 0)):
+    for field, value in (("dist", 2), ("flags", 8), ("coarse_stride", 65), ("cands_per_round", 33), ("t_steps", 0)):
         cfg = qp.qp_default_search_cfg()
         setattr(cfg, field, value)
         assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL, field
