@@ -721,12 +721,16 @@ def test_sender_path_is_bit_reproducible(qp):
     assert all(o == outs[0] for o in outs[1:])
 
 
-def test_sender_and_receiver_replay_from_a_hip_graph(qp):
+@pytest.mark.parametrize("kind,n", [("fp32", 700_003), ("fp32", 2_500_003), ("bf16", 1_300_003)],
+                         ids=["tile_search", "streaming_search", "value_table"])
+def test_sender_and_receiver_replay_from_a_hip_graph(qp, kind, n):
     """The async entry points launch kernels only (no allocation, no memset, no host sync), so they
-    capture into a HIP graph; every replay must reproduce the eager result."""
-    x1 = si.make_config("C2", n=700_003)
-    x2 = si.make_config("C3", n=700_003)
-    n = x1.size
+    capture into a HIP graph; every replay must reproduce the eager result.  One size per search kernel."""
+    if kind == "fp32":
+        x1, x2 = si.make_config("C2", n=n), si.make_config("C3", n=n)
+    else:
+        x1 = si.make_config("C5", n=n)
+        x2 = si.f32_to_bf16_bits(si.make_config("C3", n=n))
     xin = to_dev(x1).clone()
     ws = qp.alloc_workspace(n)
     packed = qp.alloc_packed(n, 4)
