@@ -104,18 +104,11 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // ---- element loads: four consecutive elements, widened to fp32 ----------------------
 // fp32: one 16-byte load; bf16: one 8-byte load, the 16 bits become the top half.
-// load_stream is for data touched once (quantize+pack): a nontemporal load keeps it from
-// displacing what other kernels left in L2 / Infinity Cache and measurably raises HBM rate.
 template <int DT> struct Vec4;
 template <> struct Vec4<QP_F32> {
     static __device__ __forceinline__ void load(const void *base, uint64_t vec, float (&f)[4])
     {
         const float4 v = reinterpret_cast<const float4 *>(base)[vec];
-        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-    }
-    static __device__ __forceinline__ void load_stream(const void *base, uint64_t vec, float (&f)[4])
-    {
-        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(base) + vec);
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
     }
     static __device__ __forceinline__ float load1(const void *base, uint64_t i)
@@ -127,14 +120,6 @@ template <> struct Vec4<QP_BF16> {
     static __device__ __forceinline__ void load(const void *base, uint64_t vec, float (&f)[4])
     {
         const uint2 v = reinterpret_cast<const uint2 *>(base)[vec];
-        f[0] = __uint_as_float(v.x << 16);
-        f[1] = __uint_as_float(v.x & 0xffff0000u);
-        f[2] = __uint_as_float(v.y << 16);
-        f[3] = __uint_as_float(v.y & 0xffff0000u);
-    }
-    static __device__ __forceinline__ void load_stream(const void *base, uint64_t vec, float (&f)[4])
-    {
-        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(base) + vec);
         f[0] = __uint_as_float(v.x << 16);
         f[1] = __uint_as_float(v.x & 0xffff0000u);
         f[2] = __uint_as_float(v.y << 16);
