@@ -192,6 +192,11 @@ def main() -> int:
         byts = in_bytes + n * b / 8
         per_bits[str(b)] = {"pack_us": tp, "pack_GBs": byts / tp / 1e3, "unpack_us": tu, "unpack_GBs": byts / tu / 1e3}
     ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % NBUF], ws))
+    # second reference line beside the nominal 8 TB/s: what a plain device-to-device copy of a tensor of this
+    # size reaches under the same timing (one launch per tensor, rotating buffers)
+    tcopy = timed_reps(lambda r: ys[r % NBUF].copy_(xs[(r + 1) % NBUF]))
+    copy_ref = {"kernel": "torch device-to-device copy (not part of the path)", "bytes": 2 * in_bytes, "us": tcopy,
+                "GBs": 2 * in_bytes / tcopy / 1e3}
     # the histogram-fit reading of Eq. 1 works on the 2048-bin histogram only (no tensor pass)
     th = timed_reps(lambda r: qp.qp_dsaciq_hist_search_async(4, ws))
     # beyond the paper: coarse-to-fine sweep (stride 10: 11 + 19 candidates instead of 101), same winner on one-valley curves
@@ -259,6 +264,7 @@ def main() -> int:
         "dsaciq_coarse_to_fine_us_per_tensor": tc,
         "step_with_search_at_2_to_4_bit_only": {"ms_per_step": tpol / 1e3, "GBs": len(bits_set) * in_bytes / tpol / 1e3},
         "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
+        "hbm_copy_reference": copy_ref,
         "per_bitwidth": per_bits,
         "large_tensor_bf16": large,
         "small_tensor_fp32": small,
@@ -282,6 +288,8 @@ def large_tensor_leg(qp, si, torch, timed_reps, reps):
     out["stats_us"] = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
     # a bf16 tensor of this size goes through its value table: one read of the tensor (not two passes)
     out["stats_GBs"] = n * 2 / out["stats_us"] / 1e3
+    tcopy = timed_reps(lambda r: ys[(r + 1) % nb].copy_(ys[r % nb]))
+    out["hbm_copy_reference_GBs"] = 2 * n * 4 / tcopy / 1e3   # plain device-to-device copy of the fp32 output tensor
     for b in si.CONFIG_BITS["C5"]:
         packs = [qp.alloc_packed(n, b) for _ in range(nb)]
         res, q = qp.qp_dsaciq_search(xs[0], st, b, ws)

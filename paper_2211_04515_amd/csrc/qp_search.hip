@@ -508,6 +508,10 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
         if (!coarse_to_fine_supported(n, dtype, plan)) return hipErrorInvalidValue;
         return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
     }
+    // So does a full sweep short enough for one round (t + 1 <= cands_per_round): the streaming kernel's
+    // strength is many candidates held in registers, and its one-round grid is the one that faulted.
+    if (!by_values && plan.t_steps + 1u <= plan.cpr && tile_search_can_run(plan))
+        return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
     return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, by_values,
                         !value_table_ready, ws, s);
 }

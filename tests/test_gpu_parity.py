@@ -258,6 +258,27 @@ def test_search_other_step_counts(qp):
         assert res.j_star == ores.j_star and res.t_steps == t
 
 
+def test_search_short_sweep_on_a_large_tensor(qp):
+    # a sweep that fits one round of candidates (t + 1 <= cands_per_round) is scored by the tile search
+    # whatever the tensor's size
+    x = si.make_config("C3", n=2_600_011)
+    xd = to_dev(x)
+    cfg = qp.qp_default_search_cfg()
+    cfg.t_steps = 10
+    assert cfg.t_steps + 1 <= cfg.cands_per_round
+    ws = qp.alloc_workspace(x.size, cfg)
+    st = qp.qp_stats(xd, ws)
+    for bits in (2, 4):
+        print(f"[case] short sweep n={x.size} t={cfg.t_steps} bits={bits}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=cfg)
+        ores, oq, oscores = orc.dsaciq_search(x, oracle_stats_from(st), bits, cfg.t_steps)
+        off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+        scores = ws[off:off + 8 * (cfg.t_steps + 1)].cpu().numpy().view(np.float64)
+        assert np.allclose(scores, oscores, rtol=REL_SCORE_FULL, atol=0.0)
+        assert res.j_star == ores.j_star and res.t_steps == cfg.t_steps
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+
+
 @pytest.mark.parametrize("name", ["constant", "zeros", "two_point", "laplace_n1", "laplace_n5", "subnormal_values",
                                   "tiny_values", "large_values", "huge_outlier"])
 def test_search_degenerate_inputs(qp, name):
