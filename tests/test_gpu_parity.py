@@ -553,6 +553,48 @@ def test_c4_stream_first_microbatches(qp):
     assert checked >= 5 and len(seen_bits) >= 3
 
 
+@pytest.mark.timeout(900)
+def test_timed_step_configuration_on_c2(qp):
+    """The step the benchmark times: on the full ViT-Base tensor, for each of its six bitwidths, the sender
+    path (statistics, search, pack; parameters stay on the device) and the receiver, back to back on one
+    stream with one workspace; the results of every pass are checked against the oracle afterwards."""
+    x = si.make_config("C2")
+    n = x.size
+    xd = to_dev(x)
+    ws = qp.alloc_workspace(n)
+    bitset = si.CONFIG_BITS["C2"]
+    packs = {b: qp.alloc_packed(n, b) for b in bitset}
+    ys = {b: torch.empty(n, dtype=torch.float32, device="cuda") for b in bitset}
+    recs = {b: torch.zeros(32 + 56 + 8 * 101, dtype=torch.uint8, device="cuda") for b in bitset}
+    offr, offs = qp.qp_ws_offset(qp.QP_WS_RESULT), qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for b in bitset:   # no synchronisation in between: what a pass leaves is copied aside on the same stream
+        qp.qp_compress_async(xd, b, ws, packs[b], qparams_out_dev_ptr=recs[b].data_ptr())
+        qp.qp_unpack_dequant_dev(packs[b], b, recs[b].data_ptr(), ys[b])
+        recs[b][32:32 + 56].copy_(ws[offr:offr + 56])
+        recs[b][88:88 + 808].copy_(ws[offs:offs + 808])
+    torch.cuda.synchronize()
+    st = qp.read_ws(ws, qp.QP_WS_STATS, qp.qp_stats_t)
+    rc, ost = orc.stats(x)
+    check_stats_full(st, ost, x)
+    for b in bitset:
+        print(f"[case] timed step C2 bits={b}", flush=True)
+        raw = recs[b].cpu().numpy().tobytes()
+        q = qp.qp_qparams_t.from_buffer_copy(raw[:32])
+        res = qp.qp_search_result_t.from_buffer_copy(raw[32:88])
+        scores = np.frombuffer(raw[88:], dtype=np.float64)
+        assert (q.bits, q.n, res.t_steps) == (b, n, 100)
+        assert res.j_star == int(np.argmin(scores))
+        F = orc.laplace_F(b)
+        for j in sorted({0, 100, int(res.j_star)}):
+            oqj = orc.make_qparams(st.mean, F * (st.mad + j * ((st.b_r - st.mad) / 100)), b, n)
+            assert scores[j] == pytest.approx(pairwise_sq_error(x, oqj), rel=REL_SCORE_PAIRWISE)
+        oq = orc.make_qparams(st.mean, res.alpha_star, b, n)   # the oracle is given the GPU's alpha
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        codes = orc.quantize(x, oq)
+        assert np.array_equal(packs[b].cpu().numpy(), orc.pack(codes, b))
+        assert np.array_equal(ys[b].cpu().numpy(), orc.dequantize(codes, oq))
+
+
 # ----------------------------------------------------------------------------- maximum size
 
 @pytest.mark.timeout(1500)
