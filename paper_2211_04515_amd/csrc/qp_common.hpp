@@ -328,6 +328,11 @@ __device__ __forceinline__ float quant_level(float x, float lo, float hi, float 
     const float r = rintf(t);
     return fminf(fmaxf(r, 0.0f), L);            // NaN -> 0
 }
+// A value that every lane of the wave holds: moves it to a scalar register.
+__device__ __forceinline__ float wave_uniform(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v)));
+}
 // lo + c*scale rounded once.
 __device__ __forceinline__ float dequant_level(float c, float scale, float lo)
 {

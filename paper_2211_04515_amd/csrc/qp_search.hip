@@ -86,21 +86,32 @@ __global__ __launch_bounds__(kFinThreads) void k_aciq_only(ModelArgs m, qp_stats
 }
 
 // The scoring pass of one block: lanes stride over batches of kSrElems elements; for each
-// batch the round's candidates (at most 32, wave-uniform) are applied to the elements held in
+// batch the round's candidates (at most 16, wave-uniform) are applied to the elements held in
 // registers.  SHORT selects the sequence without the second clamp (see setup_candidates).
-template <int DT, int CMAX, bool SHORT>
-__device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t n, const Cand *sh_cands, uint32_t nc,
-                                           float Lf, double (&acc)[CMAX])
+template <int DT, int NC, bool SHORT, int CMAX>
+__device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t n, const Cand *sh_cands, float Lf,
+                                           double (&acc)[CMAX])
 {
     constexpr bool WEIGHTED = (DT == kValues16);
     const uint32_t tid = threadIdx.x;
+    // The round's grids, read once (LDS broadcast reads).  hi, scale and 1/scale go to scalar registers
+    // (every lane holds the same values); lo stays in a vector register because an instruction takes one
+    // scalar operand at most.  That leaves the vector registers to the running sums and the elements, so
+    // that more waves fit a SIMD.
+    Cand grid[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const Cand p = sh_cands[c];
+        grid[c].lo = p.lo;
+        grid[c].hi = wave_uniform(p.hi);
+        grid[c].scale = wave_uniform(p.scale);
+        grid[c].inv_scale = wave_uniform(p.inv_scale);
+    }
     auto score = [&](const float (&v)[kSrElems], const double (&w)[kSrElems], int ne) {
 #pragma unroll
-        for (int c = 0; c < CMAX; ++c) {
-            if ((uint32_t)c < nc) {   // wave-uniform
-                // LDS broadcast read; the compiler hoists these out of the batch loop, so the round's
-                // grids live in (wave-uniform) VGPRs and the loop body is pure vector arithmetic
-                const Cand p = sh_cands[c];
+        for (int c = 0; c < NC; ++c) {
+            {
+                const Cand p = grid[c];
 #pragma unroll
                 for (int e = 0; e < kSrElems; ++e) {
                     if (e < ne) {
@@ -132,9 +143,7 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
     };
 
     const uint64_t nbatch = n / kSrElems;
-    for (uint64_t b = (uint64_t)blockIdx.x * kSrThreads + tid; b < nbatch; b += (uint64_t)gridDim.x * kSrThreads) {
-        float v[kSrElems];
-        double w[kSrElems];
+    auto load_batch = [&](uint64_t b, float (&v)[kSrElems], double (&w)[kSrElems]) {
         if constexpr (WEIGHTED) {
             const uint32_t *cnt = reinterpret_cast<const uint32_t *>(x);
 #pragma unroll
@@ -160,6 +169,13 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
                 }
             }
         }
+    };
+    const uint64_t bstride = (uint64_t)gridDim.x * kSrThreads;
+    uint64_t b = (uint64_t)blockIdx.x * kSrThreads + tid;
+    for (; b < nbatch; b += bstride) {
+        float v[kSrElems];
+        double w[kSrElems];
+        load_batch(b, v, w);
         score(v, w, kSrElems);
     }
     // ragged tail: fewer than kSrElems elements, taken by one lane of block column 0
@@ -178,12 +194,16 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
     }
 }
 
-// CMAX: the most candidates a round can hold (sizes the register file: 2*CMAX accumulator and
-// 4*CMAX grid registers per lane).
+// CMAX: the candidates of a round (sizes the register file: 2*CMAX running-sum, CMAX + 8 other vector
+// registers and 3*CMAX scalar registers per wave).  The loop has no per-candidate tests (they would cost a
+// second register pair per running sum, and with it two of the waves that fit a SIMD), so a round scores
+// either exactly CMAX candidates (the first `full` rounds) or exactly CMAX - 1 (the others): 101 candidates
+// are 5 rounds of 13 and 3 of 12.  Where a list does not split that way every round takes CMAX and the slots
+// past the end of the list repeat the last candidate and are not stored.
 template <int DT, int CMAX>
 __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restrict__ x, uint64_t n,
-                                                           const Cand *__restrict__ cands, uint32_t ncand,
-                                                           uint32_t cpr, float Lf, double *__restrict__ partials,
+                                                           const Cand *__restrict__ cands, uint32_t ncand, uint32_t full,
+                                                           float Lf, double *__restrict__ partials,
                                                            double *__restrict__ scores, Ctl *__restrict__ ctl,
                                                            uint32_t *__restrict__ round_tickets,
                                                            qp_search_result_t *__restrict__ res,
@@ -191,8 +211,10 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
                                                            double *__restrict__ scores_by_j)
 {
     const uint32_t tid = threadIdx.x;
-    const uint32_t c0 = blockIdx.y * cpr;
-    const uint32_t nc = min(cpr, ncand - c0);
+    const bool is_full = blockIdx.y < full;
+    const uint32_t slots = is_full ? (uint32_t)CMAX : (uint32_t)CMAX - 1u;
+    const uint32_t c0 = is_full ? blockIdx.y * (uint32_t)CMAX : full * (uint32_t)CMAX + (blockIdx.y - full) * ((uint32_t)CMAX - 1u);
+    const uint32_t nc = min(slots, ncand - c0);   // slots of this round that are candidates of the list
 
     double acc[CMAX];
 #pragma unroll
@@ -200,12 +222,17 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
 
     // the round's candidate grids: one coalesced load into LDS, read back per candidate as a broadcast
     __shared__ Cand sh_cands[CMAX];
-    if (tid < nc) sh_cands[tid] = cands[c0 + tid];
+    if (tid < (uint32_t)CMAX) sh_cands[tid] = cands[min(c0 + tid, ncand - 1u)];
     const uint32_t short_seq = ctl->short_seq;
     __syncthreads();
 
-    if (short_seq) score_pass<DT, CMAX, true>(x, n, sh_cands, nc, Lf, acc);
-    else score_pass<DT, CMAX, false>(x, n, sh_cands, nc, Lf, acc);
+    if (is_full) {
+        if (short_seq) score_pass<DT, CMAX, true>(x, n, sh_cands, Lf, acc);
+        else score_pass<DT, CMAX, false>(x, n, sh_cands, Lf, acc);
+    } else if constexpr (CMAX > 1) {
+        if (short_seq) score_pass<DT, CMAX - 1, true>(x, n, sh_cands, Lf, acc);
+        else score_pass<DT, CMAX - 1, false>(x, n, sh_cands, Lf, acc);
+    }
 
     // ---- block reduction: DPP inside each wave64, one LDS row per wave ----
     __shared__ double sh[kSrThreads / kWave][CMAX];
@@ -214,10 +241,8 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     const uint32_t gx = gridDim.x;
 #pragma unroll
     for (int c = 0; c < CMAX; ++c) {
-        if ((uint32_t)c < nc) {   // wave-uniform
-            const double s = wave_sum(acc[c]);
-            if (lane == 0) sh[wave][c] = s;
-        }
+        const double s = wave_sum(acc[c]);
+        if (lane == 0) sh[wave][c] = s;
     }
     __syncthreads();
     if (tid < nc) {
@@ -381,7 +406,7 @@ struct SearchArgs {
     const void *x;
     uint64_t n;
     const Cand *cands;
-    uint32_t ncand, cpr;
+    uint32_t ncand;
     float Lf;
     double *partials, *scores;
     Ctl *ctl;
@@ -392,28 +417,66 @@ struct SearchArgs {
     double *scores_by_j;   // where a coarse-to-fine sweep scatters its scores
 };
 
-// Picks the round structure and the grid for one kernel variant and launches it.
-template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a, uint32_t cpr_limit, hipStream_t s)
+// One kernel variant: the grid is one wave of resident blocks, split over the rounds.
+template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a, hipStream_t s)
 {
-    // Rounds of (nearly) equal size: 101 candidates at 16 per round -> 15,15,15,14,14,14,14.  A tensor
-    // too small to fill the device with that many rounds is cut into more, shorter rounds instead
-    // (the caller's cands_per_round is an upper bound and never changes results).
     const uint32_t resident = resident_blocks<DT, CMAX>();
     const uint32_t cols = search_blocks(a.n);
-    uint32_t rounds = (a.ncand + cpr_limit - 1u) / cpr_limit;
-    if (cols * rounds < resident) {
-        rounds = resident / cols;
-        if (rounds > a.ncand) rounds = a.ncand;
-    }
-    const uint32_t cpr_eff = (a.ncand + rounds - 1u) / rounds;
-    rounds = (a.ncand + cpr_eff - 1u) / cpr_eff;   // no empty round
+    const uint32_t rounds = (a.ncand + (uint32_t)CMAX - 1u) / (uint32_t)CMAX;
+    // `full` rounds of CMAX candidates and rounds - full of CMAX - 1, if the list splits that way
+    // (ncand = full CMAX + (rounds - full)(CMAX - 1)); else every round takes CMAX and the last one is padded
+    uint32_t full = rounds;
+    if (CMAX > 1 && a.ncand >= rounds * ((uint32_t)CMAX - 1u)) full = a.ncand - rounds * ((uint32_t)CMAX - 1u);
     uint32_t gx = resident / rounds;
     if (gx > cols) gx = cols;
     if (gx < 1) gx = 1;
-    hipLaunchKernelGGL((k_search_mse<DT, CMAX>), dim3(gx, rounds), dim3(kSrThreads), 0, s, a.x, a.n, a.cands, a.ncand,
-                       cpr_eff, a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.n_total,
-                       a.scores_by_j);
+    hipLaunchKernelGGL((k_search_mse<DT, CMAX>), dim3(gx, rounds), dim3(kSrThreads), 0, s, a.x, a.n, a.cands, a.ncand, full,
+                       a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.n_total, a.scores_by_j);
     return hipGetLastError();
+}
+
+// The kernel exists for these round sizes (more candidates per round leave too few waves on a SIMD).  The
+// caller's cands_per_round is an upper bound.  Among the sizes within it: one that gives the device at least
+// two blocks per compute unit (a short tensor, such as a value table, needs many short rounds for that), then
+// the fewest candidate slots (101 candidates: 13 -> 101 slots, 16 -> 112), then the largest.  The grouping
+// never changes a candidate's score beyond the order of its fp64 partial sums.
+constexpr uint32_t kRoundSizes[] = {16u, 13u, 8u, 4u, 2u, 1u};
+#ifndef QP_SEARCH_FILL_BLOCKS
+#define QP_SEARCH_FILL_BLOCKS 512   // two blocks per compute unit
+#endif
+
+static uint32_t round_slots(uint32_t ncand, uint32_t size)
+{
+    const uint32_t rounds = (ncand + size - 1u) / size;
+    return (size > 1u && ncand >= rounds * (size - 1u)) ? ncand : rounds * size;
+}
+
+template <int DT> static hipError_t launch_rounds(const SearchArgs &a, uint32_t cpr_limit, hipStream_t s)
+{
+    const uint32_t cols = search_blocks(a.n);
+    uint32_t pick = 1u, pick_slots = 0u;
+    bool pick_fills = false;
+    for (uint32_t size : kRoundSizes) {   // descending
+        if (size > cpr_limit) continue;
+        const uint32_t rounds = (a.ncand + size - 1u) / size;
+        const bool fills = (uint64_t)cols * rounds >= (uint64_t)QP_SEARCH_FILL_BLOCKS;
+        const uint32_t slots = round_slots(a.ncand, size);
+        const bool better = pick_slots == 0u || (fills && !pick_fills) || (fills == pick_fills && fills && slots < pick_slots) ||
+                            (!fills && !pick_fills);   // nothing fills the device: the most rounds
+        if (better) {
+            pick = size;
+            pick_slots = slots;
+            pick_fills = fills;
+        }
+    }
+    switch (pick) {
+    case 16u: return launch_variant<DT, 16>(a, s);
+    case 13u: return launch_variant<DT, 13>(a, s);
+    case 8u: return launch_variant<DT, 8>(a, s);
+    case 4u: return launch_variant<DT, 4>(a, s);
+    case 2u: return launch_variant<DT, 2>(a, s);
+    default: return launch_variant<DT, 1>(a, s);
+    }
 }
 
 ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *st, uint32_t list_mode, uint32_t count)
@@ -462,7 +525,7 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
     if (e != hipSuccess) return e;
 
     const uint32_t cpr = plan.cpr;
-    SearchArgs a{x, n, cands, count, cpr, (float)((1u << plan.bits) - 1u),
+    SearchArgs a{x, n, cands, count, (float)((1u << plan.bits) - 1u),
                  reinterpret_cast<double *>(w + kOffSearchPart), scores_list, ctl, round_tickets, res,
                  reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n, scores_by_j};
     if (by_values) {
@@ -472,13 +535,9 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
         }
         a.x = value_counts;
         a.n = kNumValues16;
-        return cpr <= 16u ? launch_variant<kValues16, 16>(a, cpr, s) : launch_variant<kValues16, 32>(a, cpr, s);
+        return launch_rounds<kValues16>(a, cpr, s);
     }
-    // the 16-candidate variant keeps three waves per SIMD resident, the 32-candidate one two (forcing more
-    // waves only makes the compiler spill the accumulators)
-    if (cpr <= 16u)
-        return dtype == QP_F32 ? launch_variant<QP_F32, 16>(a, cpr, s) : launch_variant<QP_BF16, 16>(a, cpr, s);
-    return dtype == QP_F32 ? launch_variant<QP_F32, 32>(a, cpr, s) : launch_variant<QP_BF16, 32>(a, cpr, s);
+    return dtype == QP_F32 ? launch_rounds<QP_F32>(a, cpr, s) : launch_rounds<QP_BF16>(a, cpr, s);
 }
 
 hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,

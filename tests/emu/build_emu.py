@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(HERE))
 CSRC = os.path.join(ROOT, "paper_2211_04515_amd", "csrc")
 VARIANTS = {
     "default": [],
-    "streaming": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096"],
+    "streaming": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096", "-DQP_SEARCH_FILL_BLOCKS=8"],
 }
 
 

@@ -1,6 +1,6 @@
 // TEST INFRASTRUCTURE ONLY: drives the library's C ABI on the CPU emulation (host memory stands in
 // for device memory) and writes everything it produced to files, for comparison with the oracle.
-//   emu_driver <in.bin> <n> <dtype 0|1> <bits> <t_steps> <dist> <flags> <stride> <nbins> <cus> <outdir>
+//   emu_driver <in.bin> <n> <dtype 0|1> <bits> <t_steps> <dist> <flags> <stride> <nbins> <cus> <outdir> [cands_per_round]
 #include <hip/hip_runtime.h>
 
 #include <string>
@@ -26,7 +26,7 @@ static void *alloc_exact(size_t bytes)   // 16-byte aligned; the sanitizer sees 
 
 int main(int argc, char **argv)
 {
-    if (argc != 12) { fprintf(stderr, "usage: see source\n"); return 2; }
+    if (argc != 12 && argc != 13) { fprintf(stderr, "usage: see source\n"); return 2; }
     const char *in = argv[1];
     const uint64_t n = strtoull(argv[2], nullptr, 10);
     const qp_dtype dtype = (qp_dtype)atoi(argv[3]);
@@ -40,6 +40,7 @@ int main(int argc, char **argv)
     cfg.nbins = (uint32_t)atoi(argv[9]);
     emu::g_cus = atoi(argv[10]);
     const std::string out = argv[11];
+    if (argc == 13) cfg.cands_per_round = (uint32_t)atoi(argv[12]);
 
     const size_t esz = dtype == QP_BF16 ? 2 : 4;
     void *x = alloc_exact(n * esz);

@@ -110,6 +110,7 @@ static inline float emu_med3(float a, float b, float c)
 #define __builtin_amdgcn_fmed3f(a, b, c) emu_med3((a), (b), (c))
 #define __builtin_amdgcn_alignbit(hi, lo, sh) ((uint32_t)(((((uint64_t)(hi)) << 32) | (uint32_t)(lo)) >> ((sh) & 31)))
 #define __builtin_amdgcn_readlane(v, l) ((int)emu::exchange((uint32_t)(v), (l), -1, 0))
+#define __builtin_amdgcn_readfirstlane(v) ((int)emu::exchange((uint32_t)(v), 0, -1, 0))   /* every lane of the wave is active where the kernels use it */
 #define __builtin_amdgcn_update_dpp(old, v, ctrl, rm, bm, bc) ((int)emu::exchange((uint32_t)(v), -1, (ctrl), 0))
 static inline double __shfl_xor(double v, int m, int)
 {

@@ -49,13 +49,14 @@ def drivers():
     return out
 
 
-def start_driver(exe, out_dir, x, bits, t=100, dist=0, flags=0, stride=0, nbins=2048, cus=4):
+def start_driver(exe, out_dir, x, bits, t=100, dist=0, flags=0, stride=0, nbins=2048, cus=4, cpr=None):
     os.makedirs(out_dir, exist_ok=True)
     inp = os.path.join(out_dir, "in.bin")
     x.tofile(inp)
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     return subprocess.run([exe, inp, str(x.size), "1" if x.dtype == np.uint16 else "0", str(bits), str(t), str(dist),
-                           str(flags), str(stride), str(nbins), str(cus), out_dir], capture_output=True, env=env, timeout=900)
+                           str(flags), str(stride), str(nbins), str(cus), out_dir] + ([str(cpr)] if cpr else []),
+                          capture_output=True, env=env, timeout=900)
 
 
 def read_outputs(p, out_dir):
@@ -110,6 +111,9 @@ TILE_CASES = [("C1", 3_011, 2, {}, 100), ("C3", 4_999, 3, {}, 12), ("bf16", 5_34
 # the same kind of tensors through the kernels large tensors take (thresholds lowered at build time)
 STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37), ("bf16", 5_001, 4, {}, 30),
                 ("bf16", 3_000, 3, dict(dist=1), 20), ("C1", 2_049, 6, {}, 1),
+                # rounds of 1, 2, 4 and 3 candidates (cands_per_round 1, 2, 5 with 9 candidates: 4 + 3 + 2 does not split,
+                # 3 + 3 + 3 does)
+                ("C3", 4_111, 4, dict(cpr=1), 5), ("C2", 4_100, 3, dict(cpr=2), 6), ("C4", 4_321, 2, dict(cpr=5), 8),
                 # a coarse-to-fine sweep of a tensor above the tile search's size limit still runs on the tile search
                 ("C3", 9_001, 4, dict(stride=5), 40)]
 REFUSED = ("bf16", 5_000, 4, dict(stride=10), 100)
@@ -133,7 +137,7 @@ def runs(drivers, tmp_path_factory):
         flags = (1 if v.get("clip") else 0) | (2 if v.get("stride", 1) > 1 else 0) | (4 if v.get("low_bits_only") else 0)
         out_dir = os.path.join(base, case_id(tag, item[1]))
         p = start_driver(drivers[tag], out_dir, x, bits, t=t, dist=v.get("dist", 0), flags=flags,
-                         stride=v.get("stride", 0) if flags & 2 else 0, cus=4 if tag == "default" else 2)
+                         stride=v.get("stride", 0) if flags & 2 else 0, cus=4 if tag == "default" else 2, cpr=v.get("cpr"))
         return case_id(tag, item[1]), (p, out_dir, x)
 
     with ThreadPoolExecutor(max_workers=6) as ex:
