@@ -172,16 +172,9 @@ template <int DT> __device__ __forceinline__ void load16_stream(const void *base
     }
 }
 
-// ---- "last block finishes" tickets ---------------------------------------------------
-// A block publishes its partial results with a device-scope RELEASE on the ticket counter; only
-// the block that draws the last ticket pays for the ACQUIRE (cache invalidation) before it
-// reads the others' partials.  An acquire in every block would invalidate the XCD's L2 under
-// the blocks still streaming the tensor.
-#define QP_TICKET_ORDER __ATOMIC_RELEASE
-#define QP_TICKET_ACQUIRE() __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent")
-
 // ---- device-coherent accesses ---------------------------------------------------------------
-// For data that blocks of one kernel hand to each other.  The L2 of an XCD is not coherent with
+// For data that blocks of one kernel hand to each other ("the block that draws the last ticket finishes
+// the job").  The L2 of an XCD is not coherent with
 // the other XCDs' for ordinary loads and stores; a device-scope release / acquire pair repairs
 // that by writing the whole L2 back and invalidating it, which costs microseconds per block.
 // Device-scope atomic accesses go to the point of coherence themselves, so a producer that

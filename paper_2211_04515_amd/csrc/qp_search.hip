@@ -248,45 +248,48 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     if (tid < nc) {
         double s = sh[0][tid];
         for (int w = 1; w < kSrThreads / kWave; ++w) s += sh[w][tid];
-        partials[(uint64_t)(c0 + tid) * gx + blockIdx.x] = s;   // candidate-major: a candidate's partials are contiguous
+        // candidate-major: a candidate's partials are contiguous.  Device-coherent store, waited for before
+        // the ticket below: other blocks read it without any cache write-back or invalidation.
+        st_dev(&partials[(uint64_t)(c0 + tid) * gx + blockIdx.x], s);
+        wait_stores();
     }
 
     // ---- first ticket: the last block of this round adds the round's partials ----
-    // The barrier orders every lane's global writes before lane 0's device-scope release and
-    // lane 0's acquire before every lane's reads: one fencing lane per block (a device-scope
-    // release writes the XCD's L2 back; per wave that costs more than the whole reduction).
     __syncthreads();
     if (tid == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(&round_tickets[blockIdx.y], 1u, QP_TICKET_ORDER,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&round_tickets[blockIdx.y], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sh_flag = (prev == gx - 1u) ? 1u : 0u;
     }
     __syncthreads();
     if (!sh_flag) return;
-    QP_TICKET_ACQUIRE();
 
     // one wave per candidate: lanes stride over the blocks' partials (coalesced), fixed order
     for (uint32_t c = wave; c < nc; c += kSrThreads / kWave) {
-        const double *__restrict__ col = partials + (uint64_t)(c0 + c) * gx;
+        const double *col = partials + (uint64_t)(c0 + c) * gx;
         double s = 0.0;
-        for (uint32_t b = lane; b < gx; b += kWave) s += col[b];
+        for (uint32_t b = lane; b < gx; b += kWave) s += ld_dev(&col[b]);
         s = wave_sum(s);
-        if (lane == 0) scores[c0 + c] = s;
+        if (lane == 0) {
+            st_dev(&scores[c0 + c], s);
+            wait_stores();
+        }
     }
 
     // ---- second ticket: the last round to finish picks the winner ----
     __syncthreads();
     if (tid == 0) {
         round_tickets[blockIdx.y] = 0u;
-        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, QP_TICKET_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sh_flag = (prev == gridDim.y - 1u) ? 1u : 0u;
     }
     __syncthreads();
-    if (!sh_flag || wave != 0) return;
-    QP_TICKET_ACQUIRE();
-
-    const uint32_t bi = first_min_wave(scores, ncand, lane);
-    if (lane == 0) write_search_result(ctl, scores, ncand, bi, n_total, scores_by_j, res, best);
+    if (!sh_flag) return;
+    __shared__ double sh_scores[kMaxT + 1];
+    for (uint32_t j = tid; j < ncand; j += kSrThreads) sh_scores[j] = ld_dev(&scores[j]);
+    __syncthreads();
+    if (wave != 0) return;
+    const uint32_t bi = first_min_wave(sh_scores, ncand, lane);
+    if (lane == 0) write_search_result(ctl, sh_scores, ncand, bi, n_total, scores_by_j, res, best);
 }
 
 // ---- the other reading of Eq. 1: fit the Laplace pdf to the histogram -----------------
@@ -328,17 +331,22 @@ __global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__
     if (tid == 0) {
         double tot = sh[0];
         for (int w = 1; w < kHsThreads / kWave; ++w) tot += sh[w];
-        scores[j] = tot;
-        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, QP_TICKET_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+        st_dev(&scores[j], tot);
+        wait_stores();   // the score has arrived before the ticket is drawn
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sh_flag = (prev == gridDim.x - 1u) ? 1u : 0u;
     }
     __syncthreads();
-    if (!sh_flag || wave != 0) return;
-    QP_TICKET_ACQUIRE();
+    if (!sh_flag) return;
+    // the last block: every score has arrived; read them coherently
+    __shared__ double sh_scores[kMaxT + 1];
+    for (uint32_t i = tid; i < ncand; i += kHsThreads) sh_scores[i] = ld_dev(&scores[i]);
+    __syncthreads();
+    if (wave != 0) return;
 
-    uint32_t bj = first_min_wave(scores, ncand, lane);
+    uint32_t bj = first_min_wave(sh_scores, ncand, lane);
     if (lane == 0) {
-        const double s0 = scores[0];
+        const double s0 = sh_scores[0];
         if (!(s0 == s0)) bj = 0u;   // a NaN incumbent is never beaten
         qp_search_result_t r;
         r.b_e = b_e;
@@ -346,7 +354,7 @@ __global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__
         r.b_star = b_e + (double)bj * step;
         r.alpha_star = F * r.b_star;
         r.mse_aciq = s0 / (double)B;
-        r.mse_star = scores[bj] / (double)B;
+        r.mse_star = sh_scores[bj] / (double)B;
         r.j_star = bj;
         r.t_steps = t_steps;
         *res = r;
