@@ -41,7 +41,7 @@ NBUF = 16
 # HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload, scaled by
 # what the same counters read for plain device copies of the tensor in the same run (summary and
 # commands: profiles/hbm_traffic_C2_fp32.txt).  pack / unpack: mean over the six bitwidths.
-TRAFFIC_BYTES = {"search": 40.76e6, "pack": 46.61e6, "unpack": 46.75e6, "stats": 77.96e6}
+TRAFFIC_BYTES = {"search": 89.74e6, "pack": 46.61e6, "unpack": 46.75e6, "stats": 77.96e6}
 
 
 def main() -> int:
