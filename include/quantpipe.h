@@ -115,9 +115,11 @@ typedef struct {
 #define QP_SEARCH_LOW_BITS_ONLY 4u
 typedef struct {
     uint32_t t_steps;          /* 1..1023: candidates j = 0..t_steps */
-    uint32_t cands_per_round;  /* 1..32: most candidates scored per pass over the tensor (small tensors use
-                                  fewer); never changes results.  Default 13: eight even rounds of the 101
-                                  candidates, which is what the gfx950 register file likes best */
+    uint32_t cands_per_round;  /* 1..32: most candidates scored per pass over a large tensor (the library picks
+                                  a round size of 16, 13, 8, 4, 2 or 1 within it; tensors searched tile by tile
+                                  score all candidates in one pass); never changes results.  Default 13: the
+                                  101 candidates in five rounds of 13 and three of 12, which leaves seven
+                                  waves per SIMD of gfx950 */
     uint32_t nbins;            /* kept with the configuration for callers; the search itself does not use it */
     uint32_t dist;             /* QP_LAPLACE (the paper's model) or QP_GAUSS */
     uint32_t flags;            /* QP_SEARCH_* bits, 0 = the paper's method */
@@ -197,7 +199,7 @@ qp_status qp_make_qparams_clipped(double center, double alpha, double data_min, 
  * qp_quant_pack / qp_unpack_dequant (fp32 per element, fp64 sums).  The lowest score
  * wins, ties go to the smallest j, so b_E is kept unless something is strictly better.
  * A bound that is zero, negative or not finite collapses the grid onto b_E (j* = 0).
- * The tensor is read once per round of cfg->cands_per_round candidates.
+ * A large tensor is read once per round of at most cfg->cands_per_round candidates.
  * qp_dsaciq_search returns the result and the winner's grid to the host (either may be
  * NULL); the async form takes the statistics that qp_stats_async left in the same
  * workspace and leaves QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES there.
