@@ -241,6 +241,30 @@ def test_search_result_does_not_depend_on_candidates_per_round(qp):
             assert np.allclose(scores, ref[0], rtol=1e-13, atol=0.0) and res.j_star == ref[1] and bytes(q) == ref[2]
 
 
+def test_streaming_search_round_sizes(qp):
+    """A tensor large enough for the streaming kernel: every round size it is built for (16, 13, 8, 4, 2, 1
+    candidates per round, chosen from cands_per_round) gives the same scores up to the order of the sums."""
+    x = si.make_config("C2", n=2_300_011)
+    xd = to_dev(x)
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for t, cprs in ((100, (13, 32, 8, 5, 3, 1)), (111, (13, 16))):
+        ref = None
+        for cpr in cprs:
+            print(f"[case] round sizes t={t} cands_per_round={cpr}", flush=True)
+            cfg = qp.qp_default_search_cfg()
+            cfg.t_steps, cfg.cands_per_round = t, cpr
+            ws = qp.alloc_workspace(x.size, cfg)
+            st = qp.qp_stats(xd, ws)
+            res, q = qp.qp_dsaciq_search(xd, st, 3, ws, cfg=cfg)
+            scores = ws[off:off + 8 * (t + 1)].cpu().numpy().view(np.float64).copy()
+            if ref is None:
+                ref = (scores, res.j_star, bytes(q))
+                oqj = orc.make_qparams(st.mean, orc.laplace_F(3) * (st.mad + t * ((st.b_r - st.mad) / t)), 3, x.size)
+                assert scores[t] == pytest.approx(pairwise_sq_error(x, oqj), rel=REL_SCORE_PAIRWISE)
+            else:
+                assert np.allclose(scores, ref[0], rtol=1e-13, atol=0.0) and res.j_star == ref[1] and bytes(q) == ref[2]
+
+
 def test_search_other_step_counts(qp):
     x = si.make_config("C3", n=60_001)
     xd = to_dev(x)
