@@ -200,8 +200,16 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
 // either exactly CMAX candidates (the first `full` rounds) or exactly CMAX - 1 (the others): 101 candidates
 // are 5 rounds of 13 and 3 of 12.  Where a list does not split that way every round takes CMAX and the slots
 // past the end of the list repeat the last candidate and are not stored.
+// Waves per SIMD that the register allocation is held to (the common path needs 68 vector registers with
+// 13 candidates; the rarely taken full sequence may spill a few).  The value-table variant carries a weight
+// per element and is left to the compiler.
+template <int DT, int CMAX> constexpr int search_waves()
+{
+    return DT == kValues16 ? 1 : (CMAX <= 13 ? 7 : 6);
+}
+
 template <int DT, int CMAX>
-__global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restrict__ x, uint64_t n,
+__global__ __launch_bounds__(kSrThreads, (search_waves<DT, CMAX>())) void k_search_mse(const void *__restrict__ x, uint64_t n,
                                                            const Cand *__restrict__ cands, uint32_t ncand, uint32_t full,
                                                            float Lf, double *__restrict__ partials,
                                                            double *__restrict__ scores, Ctl *__restrict__ ctl,
@@ -263,17 +271,27 @@ __global__ __launch_bounds__(kSrThreads) void k_search_mse(const void *__restric
     __syncthreads();
     if (!sh_flag) return;
 
-    // one wave per candidate: lanes stride over the blocks' partials (coalesced), fixed order
-    for (uint32_t c = wave; c < nc; c += kSrThreads / kWave) {
+    // One wave per candidate (a wave takes candidates wave, wave + 4, ...): lanes stride over the blocks'
+    // partials (coalesced), each lane adds its own in ascending order, then the wave's lanes are added.
+    // A coherent load is a round trip to the point of coherence, so a candidate's loads are issued four at
+    // a time before the first is used (one group when the grid has at most 256 columns, the usual case), and
+    // the scores are waited for once.
+    constexpr uint32_t kWaves = kSrThreads / kWave;
+    for (uint32_t c = wave; c < nc; c += kWaves) {
         const double *col = partials + (uint64_t)(c0 + c) * gx;
         double s = 0.0;
-        for (uint32_t b = lane; b < gx; b += kWave) s += ld_dev(&col[b]);
-        s = wave_sum(s);
-        if (lane == 0) {
-            st_dev(&scores[c0 + c], s);
-            wait_stores();
+        for (uint32_t b0 = lane; b0 < gx; b0 += 4u * kWave) {
+            double v[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) v[k] = (b0 + kWave * k < gx) ? ld_dev(&col[b0 + kWave * k]) : 0.0;
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (b0 + kWave * k < gx) s += v[k];
         }
+        s = wave_sum(s);
+        if (lane == 0) st_dev(&scores[c0 + c], s);
     }
+    if (lane == 0) wait_stores();
 
     // ---- second ticket: the last round to finish picks the winner ----
     __syncthreads();
