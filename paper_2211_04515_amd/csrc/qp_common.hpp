@@ -412,17 +412,25 @@ __device__ inline void finalize_stats_block(const Part1 *__restrict__ part1, uin
     __shared__ Part2 f2[kFinThreads / kWave];
     __shared__ uint32_t fpk[kFinThreads / kWave];
     const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const Part1 a = reduce_part1_block<kFinThreads>(part1, nb1, f1);
+    // The pass-2 partials and the histogram are requested before the pass-1 partials are reduced (that
+    // reduction holds a barrier, which loads do not cross by themselves): one trip to memory, not three.
+    static_assert(kMaxStat2Blocks <= kFinThreads && kMaxBins <= 8 * kFinThreads, "one partial and eight bins per lane");
     Part2 q{0.0, 0.0};
-    for (uint32_t i = tid; i < nb2; i += kFinThreads) {
-        Part2 p;
-        if constexpr (DEV) p = Part2{ld_dev(&part2[i].dev), ld_dev(&part2[i].sq)};
-        else p = part2[i];
-        q.dev += p.dev;
-        q.sq += p.sq;
+    if (tid < nb2) {
+        if constexpr (DEV) q = Part2{ld_dev(&part2[tid].dev), ld_dev(&part2[tid].sq)};
+        else q = part2[tid];
     }
+    uint32_t h[8];
+#pragma unroll
+    for (uint32_t k = 0; k < 8; ++k) {
+        const uint32_t b = tid + k * kFinThreads;
+        h[k] = 0u;
+        if (b < nbins) h[k] = DEV ? ld_dev(&hist[b]) : hist[b];
+    }
+    const Part1 a = reduce_part1_block<kFinThreads>(part1, nb1, f1);
     uint32_t peak = 0u;
-    for (uint32_t b = tid; b < nbins; b += kFinThreads) peak = max(peak, DEV ? ld_dev(&hist[b]) : hist[b]);
+#pragma unroll
+    for (uint32_t k = 0; k < 8; ++k) peak = max(peak, h[k]);
     q.dev = wave_sum(q.dev);
     q.sq = wave_sum(q.sq);
     peak = wave_max_u32(peak);
