@@ -453,6 +453,9 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
     // (ncand = full CMAX + (rounds - full)(CMAX - 1)); else every round takes CMAX and the last one is padded
     uint32_t full = rounds;
     if (CMAX > 1 && a.ncand >= rounds * ((uint32_t)CMAX - 1u)) full = a.ncand - rounds * ((uint32_t)CMAX - 1u);
+    // a list that fits one round is the tile search's job (launch_search sends it there); this kernel has
+    // only ever run with two rounds or more
+    if (rounds < 2u) return hipErrorInvalidValue;
     uint32_t gx = resident / rounds;
     if (gx > cols) gx = cols;
     if (gx < 1) gx = 1;
