@@ -7,12 +7,14 @@
 // quantization error it causes on the real tensor.  This is plain vector-ALU work (eight
 // lane operations per element and candidate, no contraction), so the kernel is organised
 // around registers, not bandwidth:
-//   - the candidates are cut into rounds of (nearly) equal size; blockIdx.y selects the
-//     round, so the whole search is one launch and the tensor is read once per round
-//     (from L2 / Infinity Cache after the first);
-//   - a lane keeps 8 elements in VGPRs and runs the round's candidates over them; the
-//     candidates' grids come from LDS once and then live in wave-uniform VGPRs, the running
-//     sums are fp64 accumulators in VGPRs: the inner loop touches no memory;
+//   - the candidates are cut into rounds of exactly 13 or 12 (101 = 5 x 13 + 3 x 12; other round sizes
+//     for other lists); blockIdx.y selects the round, so the whole search is one launch and the
+//     tensor is read once per round (mostly from L2 / Infinity Cache after the first);
+//   - a lane keeps 8 elements in VGPRs and runs the round's candidates over them; a candidate's
+//     grid is read from LDS once: lo lives in a VGPR, hi, scale and 1/scale in SGPRs, the running
+//     sums are fp64 accumulators in VGPRs: the inner loop touches no memory and holds no
+//     per-candidate test, the kernel needs 68 VGPRs and seven waves fit a SIMD (the sequence is a
+//     dependent chain per element: its issue rate depends on how many waves interleave);
 //   - the grid is sized to the number of blocks the device keeps resident (one wave of
 //     blocks, no tail);
 //   - per-block partial sums go to the workspace, candidate-major; the last block of a round
