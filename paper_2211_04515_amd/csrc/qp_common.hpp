@@ -583,64 +583,88 @@ struct ModelArgs {
     double C;
 };
 
-// Run by a whole block: candidate i of the list gets the grid of scale s_j = s_E + j (s_R - s_E)/t,
-// alpha_j = C s_j, centred on the mean (Eq. 1).  A bound or estimate that is zero, negative or not
-// finite collapses the grid onto s_E.  Writes the table to cands_a (and cands_b if given), the
-// control record if given, and before a coarse sweep fills scores_by_j with NaN ("not evaluated").
-//
-// Returns (to every lane) whether the search may use its short per-element sequence.  The full
-// sequence clamps twice: x to [lo, hi] before the subtraction and the rounded level to [0, L]
-// after it.  With x already clamped, d = x - lo lies in [0, fl(hi - lo)], t = d*inv is monotone
-// in d (inv >= 0) and rounding is monotone, so the level lies in [0, rint(fl(fl(hi - lo)*inv))]:
-// if that upper end, evaluated here in the kernels' own fp32 arithmetic, is at most L for every
-// candidate (it is whenever the range is a normal number), the second clamp can never act.
+// The scalars every candidate of a search shares: the centre, the two ends of the scale grid and its step
+// (Eq. 1), and the data's range.  A bound or estimate that is zero, negative or not finite collapses the
+// grid onto s_E (step 0).
+struct GridModel {
+    double mean, s_e, s_r, step;
+    float clo, chi;
+};
+__device__ inline GridModel grid_model(const ModelArgs &m, const qp_stats_t *st)
+{
+    GridModel g{m.mean_h, m.s_e_h, m.s_r_h, 0.0, m.clip_lo_h, m.clip_hi_h};
+    if (st) {
+        g.mean = st->mean;
+        scale_ends(*st, m.dist, g.s_e, g.s_r);
+        g.clo = (float)st->min;
+        g.chi = (float)st->max;
+    }
+    g.step = (g.s_r - g.s_e) / (double)m.t_steps;
+    const bool ok = (g.s_e > 0.0) && (g.s_r > 0.0) && isfinite(g.s_r) && isfinite(g.s_e) && isfinite(g.step);
+    if (!ok) g.step = 0.0;
+    return g;
+}
+
+// The grid of candidate j: scale s_j = s_E + j step, alpha_j = C s_j, centred on the mean (Eq. 1).
+// `safe` tells whether the search may use its short per-element sequence for it.  The full sequence
+// clamps twice: x to [lo, hi] before the subtraction and the rounded level to [0, L] after it.  With x
+// already clamped, d = x - lo lies in [0, fl(hi - lo)], t = d*inv is monotone in d (inv >= 0) and rounding
+// is monotone, so the level lies in [0, rint(fl(fl(hi - lo)*inv))]: if that upper end, evaluated here in
+// the kernels' own fp32 arithmetic, is at most L (it is whenever the range is a normal number), the second
+// clamp can never act.
+__device__ inline Cand candidate_grid(const ModelArgs &m, const GridModel &g, uint32_t j, int &safe)
+{
+    const double s_j = g.s_e + (double)j * g.step;
+    Cand c;
+    make_grid(g.mean, m.C * s_j, m.bits, c.lo, c.hi, c.scale, c.inv_scale, m.clip != 0u, g.clo, g.chi);
+    const float Lf = (float)((1u << m.bits) - 1u);
+    const float top = rintf((c.hi - c.lo) * c.inv_scale);
+    safe = (isfinite(c.lo) && isfinite(c.hi) && top >= 0.0f && top <= Lf) ? 1 : 0;
+    return c;
+}
+
+// The control record of a search, written by one lane.
+__device__ inline void write_ctl(Ctl *ctl, const ModelArgs &m, const GridModel &g, int safe, uint32_t j1, uint64_t n)
+{
+    ctl->ticket_search = 0u;
+    ctl->short_seq = (uint32_t)safe;
+    ctl->clip = m.clip;
+    ctl->b_e = g.s_e;
+    ctl->b_r = g.s_r;
+    ctl->step = g.step;
+    ctl->F = m.C;
+    ctl->mean = g.mean;
+    ctl->bits = m.bits;
+    ctl->t_steps = m.t_steps;
+    ctl->n = n;
+    ctl->list_mode = m.list_mode;
+    ctl->list_stride = m.list_stride;
+    ctl->list_j1 = j1;
+    ctl->clip_lo = g.clo;
+    ctl->clip_hi = g.chi;
+}
+
+// Run by a whole block: candidate i of the list gets the grid of its index j (list_index).  Writes the
+// table to cands_a (and cands_b if given), the control record if given, and before a coarse sweep fills
+// scores_by_j with NaN ("not evaluated").  Returns (to every lane) whether the search may use its short
+// per-element sequence for every candidate of the list.
 __device__ inline int setup_candidates(const ModelArgs &m, const qp_stats_t *st, uint32_t j1, uint64_t n, Cand *cands_a,
                                        Cand *cands_b, Ctl *ctl, double *scores_by_j)
 {
-    double mean = m.mean_h, s_e = m.s_e_h, s_r = m.s_r_h;
-    float clo = m.clip_lo_h, chi = m.clip_hi_h;
-    if (st) {
-        mean = st->mean;
-        scale_ends(*st, m.dist, s_e, s_r);
-        clo = (float)st->min;
-        chi = (float)st->max;
-    }
-    double step = (s_r - s_e) / (double)m.t_steps;
-    const bool ok = (s_e > 0.0) && (s_r > 0.0) && isfinite(s_r) && isfinite(s_e) && isfinite(step);
-    if (!ok) step = 0.0;
-    const float Lf = (float)((1u << m.bits) - 1u);
+    const GridModel g = grid_model(m, st);
     int safe = 1;
     for (uint32_t i = threadIdx.x; i < m.count; i += blockDim.x) {
         const uint32_t j = list_index(m.list_mode, m.list_stride, j1, m.t_steps, i);
-        const double s_j = s_e + (double)j * step;
-        Cand c;
-        make_grid(mean, m.C * s_j, m.bits, c.lo, c.hi, c.scale, c.inv_scale, m.clip != 0u, clo, chi);
+        int ok;
+        const Cand c = candidate_grid(m, g, j, ok);
         cands_a[i] = c;
         if (cands_b) cands_b[i] = c;
-        const float top = rintf((c.hi - c.lo) * c.inv_scale);
-        if (!(isfinite(c.lo) && isfinite(c.hi) && top >= 0.0f && top <= Lf)) safe = 0;
+        if (!ok) safe = 0;
     }
     if (scores_by_j && m.list_mode == kListCoarse)
         for (uint32_t j = threadIdx.x; j <= m.t_steps; j += blockDim.x) scores_by_j[j] = __longlong_as_double(0x7ff8000000000000ll);
     safe = __syncthreads_and(safe);
-    if (ctl && threadIdx.x == 0) {
-        ctl->ticket_search = 0u;
-        ctl->short_seq = (uint32_t)safe;
-        ctl->clip = m.clip;
-        ctl->b_e = s_e;
-        ctl->b_r = s_r;
-        ctl->step = step;
-        ctl->F = m.C;
-        ctl->mean = mean;
-        ctl->bits = m.bits;
-        ctl->t_steps = m.t_steps;
-        ctl->n = n;
-        ctl->list_mode = m.list_mode;
-        ctl->list_stride = m.list_stride;
-        ctl->list_j1 = j1;
-        ctl->clip_lo = clo;
-        ctl->clip_hi = chi;
-    }
+    if (ctl && threadIdx.x == 0) write_ctl(ctl, m, g, safe, j1, n);
     return safe;
 }
 
@@ -676,6 +700,8 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
 bool uses_value_table(uint64_t n, int dtype);
 hipError_t launch_value_table(const void *x, uint64_t n, void *ws, hipStream_t s);
 hipError_t launch_stats_from_table(uint64_t n, uint32_t nbins, void *ws, hipStream_t s);
+// The directed search over the value table (which must be built): one launch, no set-up kernel.
+hipError_t launch_table_search(uint64_t n, const SearchPlan &plan, const qp_stats_t *stats_host_or_null, void *ws, hipStream_t s);
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan);
 // The host's part of ModelArgs for one sweep of a plan.
 ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *stats_host_or_null, uint32_t list_mode, uint32_t count);

@@ -1,6 +1,6 @@
 // Step 2b: DS-ACIQ directed search (Sec. 3, Eq. 1): the streaming kernel for large tensors (above
 // 2^21 elements; smaller ones, and every coarse-to-fine sweep, take the tile search in
-// qp_search_tile.hip; large bf16 tensors are searched here through their value table).
+// qp_search_tile.hip; large bf16 tensors are searched through their value table, qp_value_table.hip).
 //
 // t+1 candidate scales b_j = b_E + j (b_R - b_E)/t walk from the ACIQ estimate towards the
 // bound given by the real histogram's peak.  Each candidate is scored by the squared
@@ -29,10 +29,6 @@
 
 namespace qp {
 
-// Internal pseudo element type: the "tensor" is the table of all 65536 bfloat16 bit patterns and
-// x points at their counts (see k_value_hist_bf16); element i has the value of pattern i and the
-// weight counts[i].
-constexpr int kValues16 = 2;
 constexpr int kSrThreads = 256;
 constexpr int kSrElems = 8;   // elements per lane per batch (two 4-element vectors)
 
@@ -94,7 +90,6 @@ template <int DT, int NC, bool SHORT, int CMAX>
 __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t n, const Cand *sh_cands, float Lf,
                                            double (&acc)[CMAX])
 {
-    constexpr bool WEIGHTED = (DT == kValues16);
     const uint32_t tid = threadIdx.x;
     // The round's grids, read once (LDS broadcast reads).  hi, scale and 1/scale go to scalar registers
     // (every lane holds the same values); lo stays in a vector register because an instruction takes one
@@ -109,90 +104,51 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
         grid[c].scale = wave_uniform(p.scale);
         grid[c].inv_scale = wave_uniform(p.inv_scale);
     }
-    auto score = [&](const float (&v)[kSrElems], const double (&w)[kSrElems], int ne) {
+    auto score = [&](const float (&v)[kSrElems], int ne) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            {
-                const Cand p = grid[c];
+            const Cand p = grid[c];
 #pragma unroll
-                for (int e = 0; e < kSrElems; ++e) {
-                    if (e < ne) {
-                        float r;
-                        if constexpr (SHORT) {
-                            // med3(x, lo, hi) == min(max(x, lo), hi) for lo <= hi, NaN -> lo as well
-                            const float xc = __builtin_amdgcn_fmed3f(v[e], p.lo, p.hi);
-                            const float d = xc - p.lo;
-                            const float t = d * p.inv_scale;
-                            r = rintf(t);
-                        } else {
-                            r = quant_level(v[e], p.lo, p.hi, p.inv_scale, Lf);
-                        }
-                        const float err = v[e] - dequant_level(r, p.scale, p.lo);
-                        if constexpr (WEIGHTED) {
-                            // count * err^2: count < 2^32 and err has 24 significant bits, so count*err
-                            // is exact in fp64 and the term is rounded once, like an unweighted one.
-                            // Patterns that do not occur (count 0; also NaN/Inf patterns) contribute nothing.
-                            const double de = (w[e] != 0.0) ? (double)err : 0.0;
-                            acc[c] = fma(w[e] * de, de, acc[c]);
-                        } else {
-                            const double de = (double)err;
-                            acc[c] = fma(de, de, acc[c]);   // de*de is exact in fp64
-                        }
+            for (int e = 0; e < kSrElems; ++e) {
+                if (e < ne) {
+                    float r;
+                    if constexpr (SHORT) {
+                        // med3(x, lo, hi) == min(max(x, lo), hi) for lo <= hi, NaN -> lo as well
+                        const float xc = __builtin_amdgcn_fmed3f(v[e], p.lo, p.hi);
+                        const float d = xc - p.lo;
+                        const float t = d * p.inv_scale;
+                        r = rintf(t);
+                    } else {
+                        r = quant_level(v[e], p.lo, p.hi, p.inv_scale, Lf);
                     }
+                    const float err = v[e] - dequant_level(r, p.scale, p.lo);
+                    const double de = (double)err;
+                    acc[c] = fma(de, de, acc[c]);   // de*de is exact in fp64
                 }
             }
         }
     };
 
     const uint64_t nbatch = n / kSrElems;
-    auto load_batch = [&](uint64_t b, float (&v)[kSrElems], double (&w)[kSrElems]) {
-        if constexpr (WEIGHTED) {
-            const uint32_t *cnt = reinterpret_cast<const uint32_t *>(x);
-#pragma unroll
-            for (int q = 0; q < kSrElems / 4; ++q) {
-                const uint4 c4 = reinterpret_cast<const uint4 *>(cnt)[(kSrElems / 4) * b + q];
-                const uint32_t cc[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t pattern = (uint32_t)(kSrElems * b) + 4 * q + e;
-                    v[4 * q + e] = __uint_as_float(pattern << 16);
-                    w[4 * q + e] = (double)cc[e];
-                }
-            }
-        } else {
-#pragma unroll
-            for (int q = 0; q < kSrElems / 4; ++q) {
-                float f[4];
-                Vec4<DT>::load(x, (kSrElems / 4) * b + q, f);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[4 * q + e] = f[e];
-                    w[4 * q + e] = 1.0;
-                }
-            }
-        }
-    };
     const uint64_t bstride = (uint64_t)gridDim.x * kSrThreads;
-    uint64_t b = (uint64_t)blockIdx.x * kSrThreads + tid;
-    for (; b < nbatch; b += bstride) {
+    for (uint64_t b = (uint64_t)blockIdx.x * kSrThreads + tid; b < nbatch; b += bstride) {
         float v[kSrElems];
-        double w[kSrElems];
-        load_batch(b, v, w);
-        score(v, w, kSrElems);
+#pragma unroll
+        for (int q = 0; q < kSrElems / 4; ++q) {
+            float f[4];
+            Vec4<DT>::load(x, (kSrElems / 4) * b + q, f);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[4 * q + e] = f[e];
+        }
+        score(v, kSrElems);
     }
     // ragged tail: fewer than kSrElems elements, taken by one lane of block column 0
-    if constexpr (!WEIGHTED) {
-        const uint32_t rem = (uint32_t)(n - nbatch * kSrElems);
-        if (rem && blockIdx.x == 0 && tid == 0) {
-            float v[kSrElems];
-            double w[kSrElems];
+    const uint32_t rem = (uint32_t)(n - nbatch * kSrElems);
+    if (rem && blockIdx.x == 0 && tid == 0) {
+        float v[kSrElems];
 #pragma unroll
-            for (int e = 0; e < kSrElems; ++e) {
-                v[e] = ((uint32_t)e < rem) ? Vec4<DT>::load1(x, nbatch * kSrElems + e) : 0.0f;
-                w[e] = 1.0;
-            }
-            score(v, w, (int)rem);
-        }
+        for (int e = 0; e < kSrElems; ++e) v[e] = ((uint32_t)e < rem) ? Vec4<DT>::load1(x, nbatch * kSrElems + e) : 0.0f;
+        score(v, (int)rem);
     }
 }
 
@@ -203,11 +159,10 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
 // are 5 rounds of 13 and 3 of 12.  Where a list does not split that way every round takes CMAX and the slots
 // past the end of the list repeat the last candidate and are not stored.
 // Waves per SIMD that the register allocation is held to (the common path needs 68 vector registers with
-// 13 candidates; the rarely taken full sequence may spill a few).  The value-table variant carries a weight
-// per element and is left to the compiler.
+// 13 candidates).
 template <int DT, int CMAX> constexpr int search_waves()
 {
-    return DT == kValues16 ? 1 : (CMAX <= 13 ? 7 : 6);
+    return CMAX <= 13 ? 7 : 6;
 }
 
 template <int DT, int CMAX>
@@ -217,7 +172,7 @@ __global__ __launch_bounds__(kSrThreads, (search_waves<DT, CMAX>())) void k_sear
                                                            double *__restrict__ scores, Ctl *__restrict__ ctl,
                                                            uint32_t *__restrict__ round_tickets,
                                                            qp_search_result_t *__restrict__ res,
-                                                           qp_qparams_t *__restrict__ best, uint64_t n_total,
+                                                           qp_qparams_t *__restrict__ best,
                                                            double *__restrict__ scores_by_j)
 {
     const uint32_t tid = threadIdx.x;
@@ -309,7 +264,7 @@ __global__ __launch_bounds__(kSrThreads, (search_waves<DT, CMAX>())) void k_sear
     __syncthreads();
     if (wave != 0) return;
     const uint32_t bi = first_min_wave(sh_scores, ncand, lane);
-    if (lane == 0) write_search_result(ctl, sh_scores, ncand, bi, n_total, scores_by_j, res, best);
+    if (lane == 0) write_search_result(ctl, sh_scores, ncand, bi, n, scores_by_j, res, best);
 }
 
 // ---- the other reading of Eq. 1: fit the Laplace pdf to the histogram -----------------
@@ -441,7 +396,6 @@ struct SearchArgs {
     uint32_t *round_tickets;
     qp_search_result_t *res;
     qp_qparams_t *best;
-    uint64_t n_total;      // elements of the tensor (differs from n only on the value-table path)
     double *scores_by_j;   // where a coarse-to-fine sweep scatters its scores
 };
 
@@ -462,7 +416,7 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
     if (gx > cols) gx = cols;
     if (gx < 1) gx = 1;
     hipLaunchKernelGGL((k_search_mse<DT, CMAX>), dim3(gx, rounds), dim3(kSrThreads), 0, s, a.x, a.n, a.cands, a.ncand, full,
-                       a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.n_total, a.scores_by_j);
+                       a.Lf, a.partials, a.scores, a.ctl, a.round_tickets, a.res, a.best, a.scores_by_j);
     return hipGetLastError();
 }
 
@@ -531,17 +485,15 @@ ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *st, uint32_t list
     return m;
 }
 
-// One sweep of the streaming search (or of the value-table search): set-up kernel, then the search kernel.
+// One sweep of the streaming search: set-up kernel, then the search kernel.
 static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
-                               uint32_t finalize_nbins, uint32_t list_mode, uint32_t count, bool by_values,
-                               bool build_value_table, void *ws, hipStream_t s)
+                               uint32_t finalize_nbins, uint32_t list_mode, uint32_t count, void *ws, hipStream_t s)
 {
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
     qp_stats_t *stats_dev = reinterpret_cast<qp_stats_t *>(w + kOffStats);
     uint32_t *round_tickets = reinterpret_cast<uint32_t *>(w + kOffRoundTickets);
-    uint32_t *value_counts = reinterpret_cast<uint32_t *>(w + kOffValueCounts);
     double *scores_by_j = reinterpret_cast<double *>(w + kOffScores);
     double *scores_list = list_mode == kListFull ? scores_by_j : reinterpret_cast<double *>(w + kOffListScores);
     qp_search_result_t *res = reinterpret_cast<qp_search_result_t *>(w + kOffResult);
@@ -552,30 +504,18 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
     const ModelArgs m = model_args(plan, st, list_mode, count);
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, m, stats_dev, n, cands, ctl, round_tickets, fin,
                        res, scores_by_j);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    const uint32_t cpr = plan.cpr;
-    SearchArgs a{x, n, cands, count, (float)((1u << plan.bits) - 1u),
-                 reinterpret_cast<double *>(w + kOffSearchPart), scores_list, ctl, round_tickets, res,
-                 reinterpret_cast<qp_qparams_t *>(w + kOffQParams), n, scores_by_j};
-    if (by_values) {
-        if (build_value_table) {
-            e = launch_value_table(x, n, ws, s);
-            if (e != hipSuccess) return e;
-        }
-        a.x = value_counts;
-        a.n = kNumValues16;
-        return launch_rounds<kValues16>(a, cpr, s);
-    }
-    return dtype == QP_F32 ? launch_rounds<QP_F32>(a, cpr, s) : launch_rounds<QP_BF16>(a, cpr, s);
+    const SearchArgs a{x, n, cands, count, (float)((1u << plan.bits) - 1u),
+                       reinterpret_cast<double *>(w + kOffSearchPart), scores_list, ctl, round_tickets, res,
+                       reinterpret_cast<qp_qparams_t *>(w + kOffQParams), scores_by_j};
+    return dtype == QP_F32 ? launch_rounds<QP_F32>(a, plan.cpr, s) : launch_rounds<QP_BF16>(a, plan.cpr, s);
 }
 
 hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
                          uint32_t finalize_nbins, bool value_table_ready, void *ws, hipStream_t s)
 {
-    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count
-    // them once (one pass over the tensor) and run the candidates over the value table.
     if (plan.aciq_only) {
         char *w = static_cast<char *>(ws);
         FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
@@ -588,9 +528,18 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
                            reinterpret_cast<qp_qparams_t *>(w + kOffQParams));
         return hipGetLastError();
     }
-    const bool by_values = uses_value_table(n, dtype);
+    // A bf16 tensor has at most 65536 distinct values: above a modest size it is cheaper to count them once
+    // (one pass over the tensor) and run the candidates over the value table.
+    if (uses_value_table(n, dtype)) {
+        if (plan.stride > 1u || finalize_nbins) return hipErrorInvalidValue;   // refused / the table path finalizes itself
+        if (!value_table_ready) {
+            const hipError_t e = launch_value_table(x, n, ws, s);
+            if (e != hipSuccess) return e;
+        }
+        return launch_table_search(n, plan, st, ws, s);
+    }
     // other small and medium tensors: one candidate per lane over LDS tiles
-    if (!by_values && tile_search_eligible(n, plan)) return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
+    if (tile_search_eligible(n, plan)) return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
     // A coarse-to-fine sweep always runs on the tile search, whatever the size (its short candidate lists
     // suit the one-candidate-per-lane layout; on this file's streaming kernel the sweep faulted the GPU once,
     // cause not found, so it is not launched from here).
@@ -600,15 +549,14 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
     }
     // So does a full sweep short enough for one round (t + 1 <= cands_per_round): the streaming kernel's
     // strength is many candidates held in registers, and its one-round grid is the one that faulted.
-    if (!by_values && plan.t_steps + 1u <= plan.cpr && tile_search_can_run(plan))
+    if (plan.t_steps + 1u <= plan.cpr && tile_search_can_run(plan))
         return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
-    return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, by_values,
-                        !value_table_ready, ws, s);
+    return launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListFull, plan.t_steps + 1u, ws, s);
 }
 
 // Whether a coarse-to-fine search of such a tensor is available: wherever the tile search can take it.  Large
-// bf16 tensors are searched through their value table (a full sweep over 65536 entries costs about 20 us, so
-// there is nothing to gain) and are refused.
+// bf16 tensors are searched through their value table (a full sweep over 65536 entries costs a few microseconds,
+// so there is nothing to gain) and are refused.
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan)
 {
     return !uses_value_table(n, dtype) && tile_search_can_run(plan);

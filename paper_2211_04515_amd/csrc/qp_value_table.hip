@@ -7,15 +7,19 @@
 // over the 65536 table entries, each weighted by its count, instead of over the tensor: the same
 // sums with equal terms grouped.  For a tensor of 151 M elements that replaces two reads of the
 // tensor for the statistics and one per search round by a single read.
+#include <type_traits>
+
 #include "qp_common.hpp"
 
 namespace qp {
 
 bool uses_value_table(uint64_t n, int dtype) { return dtype == QP_BF16 && n >= kValueTableMinN; }
 
-__global__ __launch_bounds__(1024) void k_value_table_zero(uint32_t *__restrict__ counts)
+// Also clears the search's ticket: the search over the table has no set-up launch that could.
+__global__ __launch_bounds__(1024) void k_value_table_zero(uint32_t *__restrict__ counts, Ctl *__restrict__ ctl)
 {
     reinterpret_cast<uint4 *>(counts)[blockIdx.x * 1024u + threadIdx.x] = make_uint4(0u, 0u, 0u, 0u);
+    if (blockIdx.x == 0 && threadIdx.x == 0) ctl->ticket_search = 0u;
 }
 
 // A block counts one sign (32768 patterns, 128 KB of LDS, plain u32 counters) of one chunk of the
@@ -92,7 +96,8 @@ __global__ __launch_bounds__(kVhThreads) void k_value_hist_bf16(const uint16_t *
 hipError_t launch_value_table(const void *x, uint64_t n, void *ws, hipStream_t s)
 {
     uint32_t *counts = reinterpret_cast<uint32_t *>(static_cast<char *>(ws) + kOffValueCounts);
-    hipLaunchKernelGGL(k_value_table_zero, dim3(kNumValues16 / 4096u), dim3(1024), 0, s, counts);
+    hipLaunchKernelGGL(k_value_table_zero, dim3(kNumValues16 / 4096u), dim3(1024), 0, s, counts,
+                       reinterpret_cast<Ctl *>(static_cast<char *>(ws) + kOffCtl));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const uint64_t tile = (uint64_t)kVhThreads * kVhUnroll;               // 16-byte vectors per block step
@@ -236,6 +241,105 @@ hipError_t launch_stats_from_table(uint64_t n, uint32_t nbins, void *ws, hipStre
     hipLaunchKernelGGL(k_stats_from_table, dim3(1), dim3(kTsThreads), 0, s,
                        reinterpret_cast<const uint32_t *>(w + kOffValueCounts), n, nbins,
                        reinterpret_cast<uint32_t *>(w + kOffHist), reinterpret_cast<qp_stats_t *>(w + kOffStats));
+    return hipGetLastError();
+}
+
+// ---- the directed search over the table ------------------------------------------------------
+// Eq. 1's score of a candidate is a sum over elements of a function of the value alone, so it is taken over
+// the 65536 table entries, each squared error weighted by its count: the same sum with equal terms grouped.
+// One block per candidate (t + 1 blocks of 1024 lanes, 64 entries per lane, all requested before anything
+// else).  A block builds its own candidate's grid (the arithmetic of setup_candidates), so there is no
+// set-up launch, and hands its score to the block that draws the last ticket through device-coherent
+// accesses; that block takes the first minimum and writes the control record, the result and the winner's
+// grid.  Sums in a fixed order: bit-reproducible.
+constexpr int kTbThreads = 1024;
+__global__ __launch_bounds__(kTbThreads) void k_search_table(const uint32_t *__restrict__ counts, ModelArgs m,
+                                                             const qp_stats_t *__restrict__ stats_dev, uint64_t n_total,
+                                                             Cand *__restrict__ cands, double *__restrict__ scores,
+                                                             Ctl *__restrict__ ctl, qp_search_result_t *__restrict__ res,
+                                                             qp_qparams_t *__restrict__ best)
+{
+    __shared__ double sh[kTbThreads / kWave];
+    __shared__ double sh_scores[kMaxT + 1];
+    __shared__ uint32_t sh_flag;
+    const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const uint32_t j = blockIdx.x, ncand = gridDim.x;
+    constexpr uint32_t per = kNumValues16 / kTbThreads;   // 64 table entries per lane, four consecutive ones per load
+    uint32_t cnt[per];
+#pragma unroll
+    for (uint32_t k = 0; k < per / 4; ++k) {
+        const uint4 c4 = reinterpret_cast<const uint4 *>(counts)[k * kTbThreads + tid];
+        cnt[4 * k] = c4.x;
+        cnt[4 * k + 1] = c4.y;
+        cnt[4 * k + 2] = c4.z;
+        cnt[4 * k + 3] = c4.w;
+    }
+    const GridModel g = grid_model(m, m.from_ws ? stats_dev : nullptr);
+    int safe;
+    const Cand p = candidate_grid(m, g, j, safe);
+    if (tid == 0) cands[j] = p;
+    const float Lf = (float)((1u << m.bits) - 1u);
+    double acc = 0.0;
+    auto run = [&](auto short_tag) {
+        constexpr bool SHORT = decltype(short_tag)::value;
+#pragma unroll
+        for (uint32_t k = 0; k < per; ++k) {
+            const uint32_t c = cnt[k];
+            if (c) {   // patterns that do not occur contribute nothing (NaN/Inf patterns among them, for finite tensors)
+                const float v = __uint_as_float((((k / 4) * kTbThreads + tid) * 4 + (k % 4)) << 16);
+                float r;
+                if constexpr (SHORT) {
+                    const float xc = __builtin_amdgcn_fmed3f(v, p.lo, p.hi);
+                    const float d = xc - p.lo;
+                    const float t = d * p.inv_scale;
+                    r = rintf(t);
+                } else {
+                    r = quant_level(v, p.lo, p.hi, p.inv_scale, Lf);
+                }
+                const float err = v - dequant_level(r, p.scale, p.lo);
+                // count * err^2: count < 2^32 and err has 24 significant bits, so count * err is exact in fp64
+                // and the term is rounded once, like an unweighted one
+                const double de = (double)err;
+                acc = fma((double)c * de, de, acc);
+            }
+        }
+    };
+    if (safe) run(std::true_type{});
+    else run(std::false_type{});
+    acc = wave_sum(acc);
+    if (lane == 0) sh[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double tot = sh[0];
+        for (int w = 1; w < kTbThreads / kWave; ++w) tot += sh[w];
+        st_dev(&scores[j], tot);
+        wait_stores();   // the score has arrived before the ticket is drawn
+        const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_flag = (prev == ncand - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!sh_flag) return;
+    // the last block: every score has arrived; read them coherently
+    for (uint32_t i = tid; i < ncand; i += kTbThreads) sh_scores[i] = ld_dev(&scores[i]);
+    __syncthreads();
+    if (wave != 0) return;
+    const uint32_t bi = first_min_wave(sh_scores, ncand, lane);
+    if (lane == 0) {
+        write_ctl(ctl, m, g, 1, 0u, n_total);
+        write_search_result(ctl, sh_scores, ncand, bi, n_total, scores, res, best);
+    }
+}
+
+hipError_t launch_table_search(uint64_t n, const SearchPlan &plan, const qp_stats_t *st, void *ws, hipStream_t s)
+{
+    char *w = static_cast<char *>(ws);
+    const uint32_t ncand = plan.t_steps + 1u;
+    hipLaunchKernelGGL(k_search_table, dim3(ncand), dim3(kTbThreads), 0, s,
+                       reinterpret_cast<const uint32_t *>(w + kOffValueCounts), model_args(plan, st, kListFull, ncand),
+                       reinterpret_cast<const qp_stats_t *>(w + kOffStats), n, reinterpret_cast<Cand *>(w + kOffCands),
+                       reinterpret_cast<double *>(w + kOffScores), reinterpret_cast<Ctl *>(w + kOffCtl),
+                       reinterpret_cast<qp_search_result_t *>(w + kOffResult),
+                       reinterpret_cast<qp_qparams_t *>(w + kOffQParams));
     return hipGetLastError();
 }
 
