@@ -664,8 +664,70 @@ def test_largest_supported_tensor(qp):
             assert np.array_equal(got, ref), (bits, s0)
             assert np.array_equal(y[s0:s1].cpu().numpy(), orc.dequantize(codes, oq)), (bits, s0)
         assert packed.numel() == 4 * ((n * bits + 31) // 32)
-        # the score of the winner on a periodic tensor: reps * block + remainder, from the oracle
-        e_block = pairwise_sq_error(orc.widen_bf16(block), oq)
+        # the score of the winner on a periodic tensor: periods x (one period's error) + the remainder's + the two
+        # changed elements, from the oracle
+        def err_of(bits_arr):
+            return pairwise_sq_error(orc.widen_bf16(np.ascontiguousarray(bits_arr)), oq)
+        e_total = reps * err_of(block) + err_of(block[:rem])
+        for i, v in ((12345, 40.0), (n - 2, -37.0)):
+            e_total += err_of(si.f32_to_bf16_bits(np.array([v], np.float32))) - err_of(block[i % block.size:i % block.size + 1])
+        assert res.mse_star == pytest.approx(e_total / n, rel=1e-9)
+        del packed, y
+
+
+@pytest.mark.timeout(1500)
+def test_fp32_tensor_beyond_4_gib(qp):
+    """n = 2^30 + 77 fp32 elements (4.3 GB in, byte offsets beyond 2^32): the streaming kernels of statistics,
+    search, pack and unpack with 64-bit indexing and a ragged tail.  The tensor is periodic, so the oracle's
+    sums over one period give the expected totals."""
+    n = 2 ** 30 + 77
+    rng = np.random.default_rng(7)
+    block = rng.laplace(0.05, 0.6, size=1 << 22).astype(np.float32)
+    h = np.tile(block, (n + block.size - 1) // block.size)[:n]
+    h[54321] = np.float32(33.0)       # the maximum
+    h[n - 3] = np.float32(-29.5)      # the minimum, in the ragged tail
+    print("[case] fp32 beyond 4 GiB: upload", flush=True)
+    xd = torch.from_numpy(h).cuda()
+    ws = qp.alloc_workspace(n)
+    st = qp.qp_stats(xd, ws)
+    assert st.n == n and st.n_nonfinite == 0 and (st.min, st.max) == (-29.5, 33.0)
+    b64 = block.astype(np.float64)
+    reps, rem = divmod(n, block.size)
+    changed = ((54321, 33.0), (n - 3, -29.5))
+    fix = sum(v - float(block[i % block.size]) for i, v in changed)
+    total = reps * float(b64.sum()) + float(b64[:rem].sum()) + fix
+    assert st.mean == pytest.approx(total / n, rel=1e-9, abs=1e-12)
+    dev_block = np.abs(b64 - st.mean)
+    mad = reps * float(dev_block.sum()) + float(dev_block[:rem].sum()) + sum(
+        abs(v - st.mean) - abs(float(block[i % block.size]) - st.mean) for i, v in changed)
+    assert st.mad == pytest.approx(mad / n, rel=1e-9)
+    hist_off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    assert int(ws[hist_off:hist_off + 8192].cpu().numpy().view(np.uint32).astype(np.int64).sum()) == n
+    for bits in (2, 6):
+        print(f"[case] fp32 beyond 4 GiB: bits={bits}", flush=True)
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        oq = orc.make_qparams(st.mean, res.alpha_star, bits, n)
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        # the winner's score: periods x (one period's error) + the remainder's + the two changed elements
+        def err_of(values):
+            return pairwise_sq_error(np.ascontiguousarray(values, dtype=np.float32), oq)
+        e_total = reps * err_of(block) + err_of(block[:rem]) + sum(
+            err_of(np.array([v], np.float32)) - err_of(block[i % block.size:i % block.size + 1]) for i, v in changed)
+        assert res.mse_star == pytest.approx(e_total / n, rel=1e-9)
+        packed = qp.alloc_packed(n, bits)
+        qp.qp_quant_pack(xd, q, packed)
+        y = torch.empty(n, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant(packed, q, y)
+        torch.cuda.synchronize()
+        starts = [0, 32 * 1000003, 32 * (2 ** 25 + 11), (n // 32 - 3000) * 32]   # the third lies beyond 2^32 bytes
+        for s0 in starts:
+            s1 = min(n, s0 + 32 * 4000) if s0 != starts[-1] else n
+            codes = orc.quantize(h[s0:s1], oq)
+            ref = orc.pack(codes, bits)
+            got = packed[s0 * bits // 8: s0 * bits // 8 + ref.size].cpu().numpy()
+            assert np.array_equal(got, ref), (bits, s0)
+            assert np.array_equal(y[s0:s1].cpu().numpy(), orc.dequantize(codes, oq)), (bits, s0)
+        assert packed.numel() == 4 * ((n * bits + 31) // 32)
         del packed, y
 
 
