@@ -746,7 +746,8 @@ def check_sender_result(qp, x, bits, ws, packed, t_steps=100, nbins=2048):
     for f in ("mean", "mad", "abs_mean", "var"):
         a, b = getattr(st, f), getattr(ref, f)
         scale = max(abs(b), ref.abs_mean * 1e-3 if f == "mean" else 0.0)
-        assert abs(a - b) <= REL_STATS * scale, (f, a, b)
+        # from about 10^6 terms on, the oracle's own term-by-term sums are the less exact side
+        assert abs(a - b) <= (REL_STATS if n < (1 << 19) else REL_STATS_FULL) * scale, (f, a, b)
     off = qp.qp_ws_offset(qp.QP_WS_HIST)
     hist = ws[off:off + 4 * nbins].cpu().numpy().view(np.uint32)
     assert np.array_equal(hist, hist_ref[:nbins])
