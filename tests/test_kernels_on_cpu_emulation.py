@@ -111,6 +111,8 @@ TILE_CASES = [("C1", 3_011, 2, {}, 100), ("C3", 4_999, 3, {}, 12), ("bf16", 5_34
 # the same kind of tensors through the kernels large tensors take (thresholds lowered at build time)
 STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37), ("bf16", 5_001, 4, {}, 30),
                 ("bf16", 3_000, 3, dict(dist=1), 20), ("C1", 2_049, 6, {}, 1),
+                # the search over the value table with the Gaussian model and ranges intersected with the data's
+                ("bf16", 4_500, 3, dict(dist=1, clip=True), 20),
                 # rounds of 1, 2, 4 and 3 candidates (cands_per_round 1, 2, 5 with 9 candidates: 4 + 3 + 2 does not split,
                 # 3 + 3 + 3 does)
                 ("C3", 4_111, 4, dict(cpr=1), 5), ("C2", 4_100, 3, dict(cpr=2), 6), ("C4", 4_321, 2, dict(cpr=5), 8),
