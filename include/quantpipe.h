@@ -259,6 +259,21 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
                             void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev,
                             void *stream);
 
+/* ---- the same sender path for callers that cannot allocate -----------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
+ * callers that cannot bring a workspace.  Same kernels and same results as qp_compress_async, with
+ * the workspace in a static device array inside the library (1,384,960 bytes per GPU, held until
+ * the process ends; its device address is looked up on the first call on each device).  Calls
+ * no allocating routine.  The caller still owns x_dev, packed_dev and qparams_out_dev (required:
+ * 32 bytes of device memory that receive the winner's qp_qparams_t; the statistics and the search
+ * result stay inside the library).  Limits: cfg->t_steps <= 127 (QP_ENOSPC beyond; NULL cfg =
+ * the paper's 100), any n the other calls take.  Every call on a GPU uses that GPU's one array:
+ * calls that overlap on one GPU (two streams, two threads) race; calls on one stream are safe
+ * back to back, and nothing in the array needs clearing between them. */
+qp_status qp_compress_noalloc(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
+                              const qp_search_cfg_t *cfg, void *packed_dev, size_t packed_bytes,
+                              qp_qparams_t *qparams_out_dev, void *stream);
+
 /* ---- adaptive bitwidth rule (Sec. 3 "Adaptive PDA", Eq. 2) -- host only, pure ---------
  * Given the payload size V at the current bitwidth, the microbatch size S (images), the target
  * rate R (images/s) and the measured bandwidth B, the next bitwidth is

@@ -19,7 +19,7 @@ __all__ = [
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
     "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
     "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
-    "qp_compress_async", "qp_next_bits", "qp_controller_init", "qp_controller_update", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
+    "qp_compress_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
 ]
 
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
@@ -101,6 +101,7 @@ def lib():
             "qp_unpack_dequant": (i32, [vp, sz, C.POINTER(qp_qparams_t), vp, u64, vp]),
             "qp_unpack_dequant_dev": (i32, [vp, sz, u32, vp, vp, u64, vp]),
             "qp_compress_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, sz, vp, vp]),
+            "qp_compress_noalloc": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, vp]),
             "qp_next_bits": (i32, [C.c_double, u32, C.c_double, C.c_double, C.c_double, C.POINTER(u32)]),
             "qp_controller_init": (i32, [C.POINTER(qp_controller_t), u32, C.c_double, C.c_double, u32]),
             "qp_controller_update": (i32, [C.POINTER(qp_controller_t), C.c_double, C.c_double, C.POINTER(u32)]),
@@ -117,7 +118,7 @@ def lib():
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
            "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
            "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
-           "qp_unpack_dequant_dev", "qp_compress_async", "qp_next_bits", "qp_controller_init", "qp_controller_update",
+           "qp_unpack_dequant_dev", "qp_compress_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update",
            "qp_strerror")
 
 
@@ -277,6 +278,12 @@ def qp_compress_async(x, bits: int, ws, packed, qparams_out_dev_ptr: int = 0, cf
                                    _dev(packed), packed.numel() * packed.element_size(),
                                    C.c_void_p(qparams_out_dev_ptr) if qparams_out_dev_ptr else None,
                                    _stream(stream)), "qp_compress_async")
+
+
+def qp_compress_noalloc(x, bits: int, packed, qparams_out_dev_ptr: int, cfg=None, stream=None) -> None:
+    _check(lib().qp_compress_noalloc(_dev(x), x.numel(), dtype_of(x), int(bits), _cfgp(cfg), _dev(packed),
+                                     packed.numel() * packed.element_size(), C.c_void_p(qparams_out_dev_ptr),
+                                     _stream(stream)), "qp_compress_noalloc")
 
 
 def qp_next_bits(v_bits: float, q_cur: int, s_images: float, r_images_per_s: float, bandwidth_bits_per_s: float) -> int:

@@ -1,6 +1,7 @@
 // The C ABI: argument checks, host-side scalar work (ACIQ constants, quantization grid),
 // kernel launches, result copies.  Every per-element step runs in the HIP kernels; there
 // is no CPU fallback.
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -88,6 +89,31 @@ SearchPlan make_plan(uint32_t bits, const qp_search_cfg_t *cfg)
 }
 
 qp_status hip_status(hipError_t e) { return e == hipSuccess ? QP_OK : QP_EHIP; }
+
+// ---- the sender path for callers that cannot allocate ----------------------------------------
+// The workspace of qp_compress_async, kept in the library's own image: a file-scope device array
+// (each GPU that loads the library holds its own copy until the process ends).  In host code the
+// array's name only stands for the symbol; its device address comes from hipGetSymbolAddress, once
+// per device, and that address is what is handed to the kernels.
+constexpr uint32_t kScratchMaxT = 127u;   // most search steps the static workspace is sized for
+constexpr size_t kScratchBytes = kOffSearchPart + (size_t)kMaxSearchBlocks * (kScratchMaxT + 1u) * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kScratchMaxDevices = 64;
+std::atomic<void *> scratch_ptr[kScratchMaxDevices];   // zero-initialised; a race only repeats the same query
+
+qp_status scratch_on_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return QP_EHIP;
+    if (dev < 0 || dev >= kScratchMaxDevices) return QP_EINVAL;
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QP_EHIP;
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return QP_OK;
+}
 
 }  // namespace
 
@@ -343,6 +369,23 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
                        static_cast<hipStream_t>(stream)) != hipSuccess)
         return QP_EHIP;
     return QP_OK;
+}
+
+qp_status qp_compress_noalloc(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_search_cfg_t *cfg,
+                              void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev, void *stream)
+{
+    if (!qparams_out_dev) return QP_EINVAL;   // the caller has no other way to the winner's grid
+    if (n == 0 || n > kMaxN || check_cfg(cfg) != QP_OK) return QP_EINVAL;
+    // sizes beyond what the static workspace holds
+    if (cfg && cfg->t_steps > kScratchMaxT) return QP_ENOSPC;
+    const size_t need = qp_workspace_bytes(n, cfg);
+    if (need == 0) return QP_EINVAL;
+    if (need > kScratchBytes) return QP_ENOSPC;
+    void *ws = nullptr;
+    const qp_status st = scratch_on_current_device(&ws);
+    if (st != QP_OK) return st;
+    return qp_compress_async(x_dev, n, dtype, bits, cfg, ws, kScratchBytes, packed_dev, packed_bytes, qparams_out_dev,
+                             stream);
 }
 
 qp_status qp_next_bits(double v_bits, uint32_t q_cur, double s_images, double r_images_per_s,

@@ -72,6 +72,8 @@ uint32_t exchange(uint32_t v, int src_lane_or_minus1, int ctrl, int xor_mask);
 static inline hipError_t hipGetLastError() { return hipSuccess; }
 static inline hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
 static inline hipError_t hipMemcpyAsync(void *d, const void *s, size_t n, int, hipStream_t) { memcpy(d, s, n); return hipSuccess; }
+#define HIP_SYMBOL(x) x
+template <typename T> static inline hipError_t hipGetSymbolAddress(void **p, const T &sym) { *p = (void *)&sym; return hipSuccess; }
 static inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
 static inline hipError_t hipDeviceGetAttribute(int *v, int, int) { *v = emu::g_cus; return hipSuccess; }
 template <typename K> static inline hipError_t hipOccupancyMaxActiveBlocksPerMultiprocessor(int *n, K, int, size_t) { *n = emu::g_occupancy; return hipSuccess; }

@@ -41,6 +41,19 @@ def test_library_exports_every_declared_symbol(qp):
         assert callable(getattr(qp, n))
 
 
+def test_no_alloc_entry_point_refuses_before_touching_the_gpu(qp):
+    """Sizes beyond the static workspace and bad arguments are refused by checks that precede every HIP call."""
+    L, fake, big = qp.lib(), C.c_void_p(0x10000), 1 << 40
+    cfg = qp.qp_default_search_cfg()
+    cfg.t_steps = 128
+    assert L.qp_compress_noalloc(fake, 1000, 0, 4, C.byref(cfg), fake, big, fake, None) == qp.QP_ENOSPC
+    cfg.t_steps = 0
+    assert L.qp_compress_noalloc(fake, 1000, 0, 4, C.byref(cfg), fake, big, fake, None) == qp.QP_EINVAL
+    assert L.qp_compress_noalloc(fake, 0, 0, 4, None, fake, big, fake, None) == qp.QP_EINVAL
+    assert L.qp_compress_noalloc(fake, 2 ** 32, 0, 4, None, fake, big, fake, None) == qp.QP_EINVAL
+    assert L.qp_compress_noalloc(fake, 1000, 0, 4, None, fake, big, None, None) == qp.QP_EINVAL
+
+
 def test_struct_sizes_match_the_header_layout(qp):
     assert C.sizeof(qp.qp_stats_t) == 88
     assert C.sizeof(qp.qp_qparams_t) == 32
