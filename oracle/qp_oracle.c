@@ -30,6 +30,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 /* ---- plain-data records (the oracle's own; the Python side mirrors them) ---- */
@@ -326,25 +327,41 @@ double orc_sq_error(const float *x, uint64_t n, const orc_qparams_t *q)
  * A bound that is zero, negative or not finite (or b_E <= 0) collapses the grid
  * onto b_E.  scores (t+1 doubles) receives the sums of squared errors.
  */
-int orc_dsaciq_search(const float *x, uint64_t n, const orc_stats_t *st, uint32_t bits,
-                      uint32_t t_steps, orc_search_result_t *res, orc_qparams_t *best_q,
-                      double *scores)
+/* The scale grid of Eq. 1: b_j = b_e + j step (the loop below and orc_search_candidate use it). */
+static void orc_search_grid(const orc_stats_t *st, uint32_t t_steps, double *b_e, double *b_r, double *step)
+{
+    *b_e = st->mad;
+    *b_r = st->b_r;
+    *step = (*b_r - *b_e) / (double)t_steps;
+    if (!(*b_e > 0.0) || !(*b_r > 0.0) || !isfinite(*b_r) || !isfinite(*b_e) || !isfinite(*step))
+        *step = 0.0;
+}
+
+/* The quantization grid of candidate j alone (alpha_j = F(q) b_j, centred on mu): lets a test harness
+ * score the candidates of one search separately (orc_sq_error on each), e.g. on several host threads. */
+int orc_search_candidate(const orc_stats_t *st, uint32_t bits, uint32_t t_steps, uint64_t n, uint32_t j,
+                         orc_qparams_t *q)
+{
+    if (!orc_bits_ok(bits) || t_steps == 0 || n == 0 || j > t_steps) return 2;
+    double b_e, b_r, step;
+    orc_search_grid(st, t_steps, &b_e, &b_r, &step);
+    double b_j = b_e + (double)j * step;
+    double alpha = orc_laplace_F(bits) * b_j;
+    return orc_make_qparams(st->mean, alpha, bits, n, q);
+}
+
+/* The search's decision from the t+1 scores: the lowest wins, ties go to the smallest j. */
+int orc_search_pick(const orc_stats_t *st, uint32_t bits, uint32_t t_steps, uint64_t n, const double *scores,
+                    orc_search_result_t *res, orc_qparams_t *best_q)
 {
     if (!orc_bits_ok(bits) || t_steps == 0 || n == 0) return 2;
     double F = orc_laplace_F(bits);
-    double b_e = st->mad, b_r = st->b_r;
-    double step = (b_r - b_e) / (double)t_steps;
-    if (!(b_e > 0.0) || !(b_r > 0.0) || !isfinite(b_r) || !isfinite(b_e) || !isfinite(step))
-        step = 0.0;
+    double b_e, b_r, step;
+    orc_search_grid(st, t_steps, &b_e, &b_r, &step);
     uint32_t best_j = 0;
     double best = 0.0, first = 0.0;
     for (uint32_t j = 0; j <= t_steps; ++j) {
-        double b_j = b_e + (double)j * step;
-        double alpha = F * b_j;
-        orc_qparams_t q;
-        orc_make_qparams(st->mean, alpha, bits, n, &q);
-        double s = orc_sq_error(x, n, &q);
-        if (scores) scores[j] = s;
+        double s = scores[j];
         if (j == 0) first = s;
         if (j == 0 || s < best) { best = s; best_j = j; }
     }
@@ -359,6 +376,23 @@ int orc_dsaciq_search(const float *x, uint64_t n, const orc_stats_t *st, uint32_
     res->mse_star = best / (double)n;
     if (best_q) orc_make_qparams(st->mean, res->alpha_star, bits, n, best_q);
     return 0;
+}
+
+int orc_dsaciq_search(const float *x, uint64_t n, const orc_stats_t *st, uint32_t bits,
+                      uint32_t t_steps, orc_search_result_t *res, orc_qparams_t *best_q,
+                      double *scores)
+{
+    if (!orc_bits_ok(bits) || t_steps == 0 || n == 0) return 2;
+    double *sc = scores ? scores : (double *)malloc(((size_t)t_steps + 1) * sizeof(double));
+    if (!sc) return 2;
+    for (uint32_t j = 0; j <= t_steps; ++j) {
+        orc_qparams_t q;
+        orc_search_candidate(st, bits, t_steps, n, j, &q);
+        sc[j] = orc_sq_error(x, n, &q);
+    }
+    int rc = orc_search_pick(st, bits, t_steps, n, sc, res, best_q);
+    if (!scores) free(sc);
+    return rc;
 }
 
 /* ---- Adaptive PDA bitwidth rule (Sec. 3, Eq. 2) -----------------------------

@@ -89,6 +89,12 @@ def lib():
         L.orc_dsaciq_search.argtypes = [fp, C.c_uint64, C.POINTER(Stats), C.c_uint32, C.c_uint32,
                                         C.POINTER(SearchResult), C.POINTER(QParams), dp]
         L.orc_dsaciq_search.restype = C.c_int
+        L.orc_search_candidate.argtypes = [C.POINTER(Stats), C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint32,
+                                           C.POINTER(QParams)]
+        L.orc_search_candidate.restype = C.c_int
+        L.orc_search_pick.argtypes = [C.POINTER(Stats), C.c_uint32, C.c_uint32, C.c_uint64, dp, C.POINTER(SearchResult),
+                                      C.POINTER(QParams)]
+        L.orc_search_pick.restype = C.c_int
         L.orc_hist_search.argtypes = [C.POINTER(Stats), u32p, C.c_uint32, C.c_uint32, C.POINTER(SearchResult),
                                       C.POINTER(QParams), dp]
         L.orc_hist_search.restype = C.c_int
@@ -226,6 +232,45 @@ def dsaciq_search(x, st, bits, t_steps=100):
                                  scores.ctypes.data_as(C.POINTER(C.c_double)))
     if rc:
         raise ValueError("orc_dsaciq_search: bad argument")
+    return res, q, scores
+
+
+def search_candidate(st, bits, t_steps, n, j):
+    """The grid of candidate j of the search (what orc_dsaciq_search scores at step j)."""
+    q = QParams()
+    if lib().orc_search_candidate(C.byref(st), int(bits), int(t_steps), int(n), int(j), C.byref(q)):
+        raise ValueError("orc_search_candidate: bad argument")
+    return q
+
+
+def search_pick(st, bits, t_steps, n, scores):
+    """The search's decision from all t+1 scores.  Returns (SearchResult, QParams of the winner)."""
+    sc = np.ascontiguousarray(scores, dtype=np.float64)
+    if sc.size != t_steps + 1:
+        raise ValueError("need t_steps + 1 scores")
+    res, q = SearchResult(), QParams()
+    if lib().orc_search_pick(C.byref(st), int(bits), int(t_steps), int(n), sc.ctypes.data_as(C.POINTER(C.c_double)),
+                             C.byref(res), C.byref(q)):
+        raise ValueError("orc_search_pick: bad argument")
+    return res, q
+
+
+def dsaciq_search_threads(x, st, bits, t_steps=100, threads=16):
+    """orc_dsaciq_search with its candidates spread over host threads: each candidate is scored by the
+    same orc_sq_error call, alone and in index order over the tensor (ctypes releases the interpreter
+    lock during the call), and orc_search_pick then decides.  Same values as dsaciq_search(), bit for bit;
+    the oracle's arithmetic is untouched, only the wall-clock changes."""
+    from concurrent.futures import ThreadPoolExecutor
+    a, p = _f32(x)
+    L = lib()
+
+    def one(j):
+        q = search_candidate(st, bits, t_steps, a.size, j)
+        return L.orc_sq_error(p, a.size, C.byref(q))
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        scores = np.array(list(ex.map(one, range(t_steps + 1))), dtype=np.float64)
+    res, q = search_pick(st, bits, t_steps, a.size, scores)
     return res, q, scores
 
 

@@ -750,3 +750,25 @@ def test_controller_decides_exactly_what_eq2_decides_on_the_window_averages():
             else:
                 assert q_new == q
             q = q_new
+
+
+def test_threaded_search_harness_is_the_sequential_search():
+    """dsaciq_search_threads only changes who calls orc_sq_error when: scores, winner and grid are those of
+    orc_dsaciq_search bit for bit, and orc_search_candidate / orc_search_pick are the loop's two halves."""
+    for name, n in (("C2", 50_003), ("C3", 20_001), ("C1", 7_777)):
+        x = si.make_config(name, n=n)
+        rc, st = orc.stats(x)
+        for bits, t in ((2, 100), (8, 100), (4, 7)):
+            r1, q1, s1 = orc.dsaciq_search(x, st, bits, t)
+            r2, q2, s2 = orc.dsaciq_search_threads(x, st, bits, t, threads=5)
+            assert bytes(r1) == bytes(r2) and bytes(q1) == bytes(q2) and np.array_equal(s1, s2)
+            F = orc.laplace_F(bits)
+            for j in (0, 1, t // 2, t):   # the candidate's grid is F(q) (b_E + j (b_R - b_E)/t) about the mean
+                a = orc.make_qparams(st.mean, F * (st.mad + j * ((st.b_r - st.mad) / t)), bits, x.size)
+                assert bytes(orc.search_candidate(st, bits, t, x.size, j)) == bytes(a)
+    # the decision alone: first minimum, ties to the smaller index
+    rc, st = orc.stats(si.make_config("C1", n=1000))
+    res, q = orc.search_pick(st, 4, 4, 1000, [5.0, 3.0, 3.0, 4.0, 3.0])
+    assert res.j_star == 1 and res.mse_aciq == 5.0 / 1000 and res.mse_star == 3.0 / 1000
+    res, q = orc.search_pick(st, 4, 2, 1000, [1.0, 1.0, 1.0])
+    assert res.j_star == 0
