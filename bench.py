@@ -3,17 +3,25 @@
 
 A step is one pass of the whole path (statistics -> DS-ACIQ directed search -> clip +
 quantize + pack -> unpack + dequantize) over the ViT-Base stage-boundary tensor
-64x197x768 fp32, once per bitwidth in {2,3,4,6,8,16} (six passes), with every result kept
-on the device (no host round trip inside the step).  Inputs are synthetic (seeded mixture of
-Laplace and Gaussian values with scaled outliers), resident in HBM before the timed region;
-passes rotate over 16 distinct input/output buffer sets (> 600 MB) so that the tensor is not
-served from the 256 MB Infinity Cache left warm by the previous pass.
+64x197x768 fp32 (C2: the configuration the metric is quoted on), once per bitwidth in
+{2,3,4,6,8,16} (six passes), with every result kept on the device (no host round trip inside
+the step).  Inputs are synthetic (seeded mixture of Laplace and Gaussian values with scaled
+outliers), resident in HBM before the timed region; passes rotate over 16 distinct
+input/output buffer sets (> 600 MB) so that the tensor is not served from the 256 MB
+Infinity Cache left warm by the previous pass.
 
 Prints ONE JSON line.  `value` is activation bytes entering the path per second.
 `roofline` describes the kernel that dominates the step (the directed-search kernel, bound by
 plain vector ALU work); `roofline_pack` / `roofline_unpack` / `roofline_stats` describe the
-HBM-bound kernels.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
-workload on this machine's host cores.
+HBM-bound kernels.  The other configurations ride in the same line, each with roofline-shaped
+entries of its own: `c3_vit_large_fp32` (64x197x1024 post-GELU, cands_per_round 32),
+`large_tensor_bf16` (C5: 256x577x1024 bf16, the largest, HBM-honest by itself),
+`microbatch_stream_fp32` (C4: 500 microbatches of 32x257x1280 whose bitwidth follows a
+bandwidth trace) and `small_tensor_fp32` (C1: one image, launch-bound; eager and replayed from
+a HIP graph).  `cpu_baseline` is the CPU oracle timed on a bounded sample of the C2 workload on
+this machine's host cores, single-threaded and with the harness spreading it over the cores.
+
+--legs picks a subset, e.g. `--legs c5` for a profile of the bf16 kernels alone (the timed step is the c2 leg).
 """
 from __future__ import annotations
 
@@ -37,11 +45,35 @@ HBM_PEAK_GBS = 8000.0                  # MI355X HBM3E, published
 SEARCH_LANEOPS_PER_ELEM_CAND = 8       # algorithmic vector operations per element and candidate
 VALU_PEAK_TLANEOPS = 8.0 / (6.0 / 78.64 + 2.0 / 39.32)
 NBUF = 16
+ALL_LEGS = ("c2", "c3", "c5", "c1", "c4", "cpu")
 
-# HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload, scaled by
-# what the same counters read for plain device copies of the tensor in the same run (summary and
-# commands: profiles/hbm_traffic_C2_fp32.txt).  pack / unpack: mean over the six bitwidths.
-TRAFFIC_BYTES = {"search": 89.74e6, "pack": 46.61e6, "unpack": 46.75e6, "stats": 77.96e6}
+# HBM traffic per launch as a multiple of the kernel's algorithmic bytes, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this file, each scaled by what the same counter reads for plain device copies of known
+# size inside the same run.  These are calibration constants copied from the tracked summaries named here,
+# not measured by this process: a changed kernel shows in them only when those summaries are regenerated.
+TRAFFIC_RATIO = {
+    # profiles/hbm_traffic_C2_fp32.txt
+    "c2_search_bytes": 89.74e6, "c2_pack": 1.0003, "c2_unpack": 1.003, "c2_stats": 1.0065,
+    # profiles/hbm_traffic_C5_bf16.txt
+    "c5_value_hist": 1.0, "c5_pack": 1.0, "c5_unpack": 1.0,
+}
+TRAFFIC_SOURCE = {"c2": "profiles/hbm_traffic_C2_fp32.txt", "c5": "profiles/hbm_traffic_C5_bf16.txt"}
+
+
+def hbm_entry(kernel, alg_bytes, us, traffic_ratio, source, timed):
+    a = alg_bytes / us / 1e3
+    return {"kernel": kernel, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": a / HBM_PEAK_GBS, "algorithmic_bytes": alg_bytes,
+            "traffic": None if traffic_ratio is None else alg_bytes * traffic_ratio,
+            "traffic_source": source, "us_per_launch": us, "timed": timed}
+
+
+def alu_entry(kernel, n, ncand, us, traffic, timed):
+    ops = SEARCH_LANEOPS_PER_ELEM_CAND * ncand * n
+    a = ops / (us * 1e-6) / 1e12
+    return {"kernel": kernel, "bound": "alu", "achieved": a, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+            "frac": a / VALU_PEAK_TLANEOPS, "algorithmic_laneops": ops, "traffic": traffic, "us_per_launch": us,
+            "timed": timed}
 
 
 def main() -> int:
@@ -49,22 +81,22 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-large", action="store_true", help="skip the 151M-element bf16 tensor leg")
-    ap.add_argument("--no-c4", action="store_true", help="skip the microbatch-stream leg (32x257x1280 fp32 per microbatch)")
-    ap.add_argument("--only-small", action="store_true",
-                    help="run only the 1x197x768 leg and print its figures (for a profile of the small-tensor path)")
-    ap.add_argument("--no-small", action="store_true",
-                    help="skip the 1x197x768 leg (it launches the same kernels on a small tensor, which would mix "
-                         "into a profiler's per-kernel averages)")
+    ap.add_argument("--legs", default=",".join(ALL_LEGS),
+                    help="comma-separated subset of " + ",".join(ALL_LEGS) + " (default: all).  The timed step is the "
+                         "c2 leg; without it only the chosen legs run and `value` is null (for profiles of one leg)")
     ap.add_argument("--kernel-reps", type=int, default=64, help="back-to-back launches per kernel timing")
+    ap.add_argument("--c4-microbatches", type=int, default=500)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (tensors shard by microbatch with no exchange); "
               "use --gpus 1", file=sys.stderr)
         return 2
+    legs = [l for l in args.legs.split(",") if l]
+    for l in legs:
+        if l not in ALL_LEGS:
+            print(f"bench.py: unknown leg {l!r}", file=sys.stderr)
+            return 2
 
-    import numpy as np
     import torch
 
     import paper_2211_04515_amd as qp
@@ -75,33 +107,61 @@ def main() -> int:
         return 2
     qp.lib()
     torch.cuda.set_device(0)
-    if args.only_small:
-        def reps_small(fn, R=args.kernel_reps):
-            for r in range(4):
-                fn(r)
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for r in range(R):
-                fn(r)
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b) * 1e3 / R
-        print(json.dumps({"small_tensor_fp32": small_tensor_leg(qp, si, torch, reps_small)}))
-        return 0
-    name = "C2"
-    bits_set = si.CONFIG_BITS[name]
-    x_host = si.make_config(name)
+
+    # short kernels (about 10 us): an event pair per launch would add a fifth to them, so kernel_reps
+    # back-to-back launches over rotating buffers are timed between two HIP events on the launch stream
+    # (a whole untimed repetition first: after a pause on the host the first few milliseconds of GPU work run at a
+    # lower clock, which showed as 10-15 % on the first search timed after a synchronising call)
+    def timed_reps(fn, reps=None):
+        R = reps or args.kernel_reps
+        for r in range(R):
+            fn(r)
+        torch.cuda.synchronize()
+        for r in range(R):
+            fn(r)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for r in range(R):
+            fn(r)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / R
+
+    out = {
+        "metric": "activation GB/s quantize+pack & unpack+dequant (% HBM peak); DS-ACIQ us/tensor",
+        "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+    }
+    x_c2 = None
+    if "c2" in legs:
+        x_c2 = si.make_config("C2")
+        out.update(c2_leg(qp, si, torch, x_c2, args, timed_reps))
+    if "c3" in legs:
+        out["c3_vit_large_fp32"] = c3_leg(qp, si, torch, timed_reps, args.kernel_reps)
+    if "c5" in legs:
+        out["large_tensor_bf16"] = large_tensor_leg(qp, si, torch, timed_reps, args.kernel_reps)
+    if "c1" in legs:
+        out["small_tensor_fp32"] = small_tensor_leg(qp, si, torch, timed_reps)
+    if "c4" in legs:
+        out["microbatch_stream_fp32"] = c4_stream_leg(qp, si, torch, args.c4_microbatches)
+    if "cpu" in legs:
+        out["cpu_baseline"] = cpu_baseline(x_c2 if x_c2 is not None else si.make_config("C2"), si.CONFIG_BITS["C2"])
+    print(json.dumps(out))
+    return 0
+
+
+def c2_leg(qp, si, torch, x_host, args, timed_reps):
+    """The timed step (whole path, six bitwidths) and the per-kernel rooflines on the ViT-Base tensor."""
+    bits_set = si.CONFIG_BITS["C2"]
     n = x_host.size
     in_bytes = n * 4
-
     xs = [torch.from_numpy(x_host).cuda() for _ in range(NBUF)]
     ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(NBUF)]
     packs = {b: [qp.alloc_packed(n, b) for _ in range(NBUF)] for b in bits_set}
     ws = qp.alloc_workspace(n)
     qdev = ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-
     counter = [0]
 
     def one_pass(bits, timers=None):
@@ -151,38 +211,17 @@ def main() -> int:
         step(timers)
     torch.cuda.synchronize()
     ms_per_step_instrumented = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # stage durations from the HIP events of the instrumented repetition (torch's current stream, which is
-    # the stream the kernels are launched on)
     stage = {"stats": [], "search": [], "pack": [], "unpack": []}
     for bits, e in timers:
         for k, s in enumerate(("stats", "search", "pack", "unpack")):
             stage[s].append(e[k].elapsed_time(e[k + 1]) * 1e3)
     mean = lambda v: float(sum(v) / len(v))
     search_us = mean(stage["search"])       # setup kernel (a few microseconds) + search kernel
-    search_ops = SEARCH_LANEOPS_PER_ELEM_CAND * 101 * n
-    roofline = {"kernel": "k_search_mse<fp32> (+ k_search_setup)", "bound": "alu",
-                "achieved": search_ops / (search_us * 1e-6) / 1e12, "peak": VALU_PEAK_TLANEOPS,
-                "unit": "Tlaneop/s", "frac": None, "traffic": TRAFFIC_BYTES["search"],
-                "us_per_launch": search_us,
-                "timed": "HIP events around every search launch in an instrumented repetition of the timed steps"}
-    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline = alu_entry("k_search_mse<fp32,13> (+ k_search_setup)", n, 101, search_us, TRAFFIC_RATIO["c2_search_bytes"],
+                         "HIP events around every search launch in an instrumented repetition of the timed steps")
+    roofline["traffic_source"] = TRAFFIC_SOURCE["c2"]
 
-    # the HBM-bound kernels: short (about 10 us), so an event pair per launch would add a fifth to
-    # them; time kernel_reps back-to-back launches over rotating buffers between two events
-    def timed_reps(fn):
-        R = args.kernel_reps
-        for r in range(4):
-            fn(r)
-        torch.cuda.synchronize()
-        a, b = ev(), ev()
-        a.record()
-        for r in range(R):
-            fn(r)
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e3 / R
-
+    rot = f"{args.kernel_reps} back-to-back launches over {NBUF} rotating buffer sets between two HIP events"
     per_bits = {}
     for b in bits_set:
         q = qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)
@@ -190,7 +229,9 @@ def main() -> int:
         tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % NBUF], q, packs[b][r % NBUF]))
         tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[b][r % NBUF], q, ys[r % NBUF]))
         byts = in_bytes + n * b / 8
-        per_bits[str(b)] = {"pack_us": tp, "pack_GBs": byts / tp / 1e3, "unpack_us": tu, "unpack_GBs": byts / tu / 1e3}
+        per_bits[str(b)] = {"pack_us": tp, "pack_GBs": byts / tp / 1e3, "pack_frac_hbm": byts / tp / 1e3 / HBM_PEAK_GBS,
+                            "unpack_us": tu, "unpack_GBs": byts / tu / 1e3,
+                            "unpack_frac_hbm": byts / tu / 1e3 / HBM_PEAK_GBS}
     ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % NBUF], ws))
     # second reference line beside the nominal 8 TB/s: what a plain device-to-device copy of a tensor of this
     # size reaches under the same timing (one launch per tensor, rotating buffers)
@@ -215,106 +256,160 @@ def main() -> int:
             qp.qp_unpack_dequant_dev(packs[b][r % NBUF], b, qdev, ys[r % NBUF])
     tpol = timed_reps(policy_step)
 
-    def hbm(kernel, byts, us, key):
-        a = byts / us / 1e3
-        return {"kernel": kernel, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": a / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES[key], "us_per_launch": us,
-                "timed": f"{args.kernel_reps} back-to-back launches over {NBUF} rotating buffer sets between two HIP events"}
+    # Where the floor of a launch of this size is: the same two kernels at 4 bit on 1, 2, 4 and 8 copies of the tensor
+    # laid end to end (38.7 to 310 MB in), each size over enough rotating buffers to exceed the Infinity Cache;
+    # least-squares fit of us = fixed + bytes / rate.  The fixed part (launch, ramp to full bandwidth, drain) is what
+    # keeps a 40 MB launch below the rate the same kernel reaches on a large tensor.
+    sweep = size_sweep(qp, torch, x_host, timed_reps)
 
     # headline for pack / unpack: the mean over the six bitwidths of the workload
     pack_bytes = sum(in_bytes + n * b / 8 for b in bits_set)
     pack_us = sum(per_bits[str(b)]["pack_us"] for b in bits_set)
     unpack_us = sum(per_bits[str(b)]["unpack_us"] for b in bits_set)
-    r_pack = hbm("k_quant_pack<k,fp32>, k in {2,3,4,6,8,16}", pack_bytes / len(bits_set), pack_us / len(bits_set), "pack")
-    r_unpack = hbm("k_unpack_dequant<k>, k in {2,3,4,6,8,16}", pack_bytes / len(bits_set), unpack_us / len(bits_set), "unpack")
-    r_stats = hbm("k_stats_pass1 + k_stats_pass2", 2 * in_bytes, ts, "stats")
-
-    # the large bf16 tensor (256x577x1024, 302 MB in: larger than the Infinity Cache by itself):
-    # the HBM-honest reading of the same two kernels, kernel-only
-    large = None
-    if not args.no_large:
-        del xs, ys, packs
-        torch.cuda.empty_cache()
-        large = large_tensor_leg(qp, si, torch, timed_reps, args.kernel_reps)
-
-    # one image's activations (1x197x768 fp32): the whole sender path per tensor, launch-bound
-    small = None if args.no_small else small_tensor_leg(qp, si, torch, timed_reps)
-
-    # a stream of microbatches whose bitwidth follows a bandwidth trace: sustained time per microbatch
-    c4 = None
-    if not args.no_c4 and not args.no_large:
-        c4 = c4_stream_leg(qp, si, torch)
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(x_host, bits_set)
-
-    out = {
-        "metric": "activation GB/s quantize+pack & unpack+dequant (% HBM peak); DS-ACIQ us/tensor",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "C2: ViT-Base stage boundary 64x197x768 fp32, 70% Laplace(0,0.4)/30% N(0.1,1) + 0.05% outliers x30, "
-                               "full path (stats, DS-ACIQ t=100, pack, unpack) once per bitwidth in {2,3,4,6,8,16}",
-                   "elements": n, "bitwidths": list(bits_set), "passes_per_step": len(bits_set), "buffers_rotated": NBUF},
+    nb = len(bits_set)
+    r_pack = hbm_entry("k_quant_pack<k,fp32>, k in {2,3,4,6,8,16}", pack_bytes / nb, pack_us / nb, TRAFFIC_RATIO["c2_pack"],
+                       TRAFFIC_SOURCE["c2"], rot)
+    r_unpack = hbm_entry("k_unpack_dequant<k>, k in {2,3,4,6,8,16}", pack_bytes / nb, unpack_us / nb,
+                         TRAFFIC_RATIO["c2_unpack"], TRAFFIC_SOURCE["c2"], rot)
+    r_stats = hbm_entry("k_stats_pass1 + k_stats_pass2", 2 * in_bytes, ts, TRAFFIC_RATIO["c2_stats"], TRAFFIC_SOURCE["c2"], rot)
+    return {
+        "value": value, "ms_per_step": ms_per_step,
+        "config": {"workload": "C2 (the configuration the metric is quoted on): ViT-Base stage boundary 64x197x768 fp32, "
+                               "70% Laplace(0,0.4)/30% N(0.1,1) + 0.05% outliers x30, full path (stats, DS-ACIQ t=100, pack, "
+                               "unpack) once per bitwidth in {2,3,4,6,8,16}; the largest single-GPU configuration (C5, "
+                               "256x577x1024 bf16) is the large_tensor_bf16 entry of this line",
+                   "elements": n, "bitwidths": list(bits_set), "passes_per_step": nb, "buffers_rotated": NBUF},
+        "value_is": "activation bytes entering the whole path per second; the metric's named rates (quantize+pack, "
+                    "unpack+dequantize GB/s and % of HBM peak, DS-ACIQ us per tensor) are roofline_pack, roofline_unpack "
+                    "and dsaciq_us_per_tensor",
         "ms_per_step_instrumented": ms_per_step_instrumented,
         "stage_us": {k: mean(v) for k, v in stage.items()},
         "dsaciq_us_per_tensor": search_us,
         "dsaciq_histogram_fit_us_per_tensor": th,
         "dsaciq_coarse_to_fine_us_per_tensor": tc,
-        "step_with_search_at_2_to_4_bit_only": {"ms_per_step": tpol / 1e3, "GBs": len(bits_set) * in_bytes / tpol / 1e3},
+        "step_with_search_at_2_to_4_bit_only": {"ms_per_step": tpol / 1e3, "GBs": nb * in_bytes / tpol / 1e3},
         "roofline": roofline, "roofline_pack": r_pack, "roofline_unpack": r_unpack, "roofline_stats": r_stats,
         "hbm_copy_reference": copy_ref,
         "per_bitwidth": per_bits,
-        "large_tensor_bf16": large,
-        "small_tensor_fp32": small,
-        "microbatch_stream_fp32": c4,
-        "cpu_baseline": cpu,
+        "size_sweep_4bit": sweep,
     }
-    print(json.dumps(out))
-    return 0
+
+
+def size_sweep(qp, torch, x_host, timed_reps):
+    import numpy as np
+    n1 = x_host.size
+    rows, pts_p, pts_u = [], [], []
+    for m in (1, 2, 4, 8):
+        n = n1 * m
+        nb = max(3, 16 // m)
+        xs = [torch.from_numpy(x_host).cuda().repeat(m) for _ in range(nb)]
+        ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(nb)]
+        pk = [qp.alloc_packed(n, 4) for _ in range(nb)]
+        q = qp.qp_make_qparams(0.0, 2.5, 4, n)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, pk[r % nb]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(pk[r % nb], q, ys[r % nb]))
+        byts = n * 4 + n * 4 / 8
+        rows.append({"elements": n, "bytes": byts, "pack_us": tp, "pack_frac_hbm": byts / tp / 1e3 / HBM_PEAK_GBS,
+                     "unpack_us": tu, "unpack_frac_hbm": byts / tu / 1e3 / HBM_PEAK_GBS})
+        pts_p.append((byts, tp))
+        pts_u.append((byts, tu))
+        del xs, ys, pk
+
+    def fit(pts):
+        a = np.array([[1.0, b] for b, _ in pts])
+        t = np.array([u for _, u in pts])
+        (fixed, slope), *_ = np.linalg.lstsq(a, t, rcond=None)
+        return {"fixed_us": float(fixed), "asymptotic_GBs": float(1.0 / slope / 1e3),
+                "asymptotic_frac_hbm": float(1.0 / slope / 1e3 / HBM_PEAK_GBS)}
+    return {"sizes": rows, "fit_pack": fit(pts_p), "fit_unpack": fit(pts_u)}
+
+
+def c3_leg(qp, si, torch, timed_reps, reps):
+    """C3: the ViT-Large stage boundary 64x197x1024 fp32 after a GELU (one-sided, spike near zero), searched with
+    cands_per_round = 32 as the configuration names it (an upper bound to the library, which takes rounds of 13 / 12
+    candidates: more per round leaves too few waves per SIMD), bitwidths {2,4,8}."""
+    x = si.make_config("C3")
+    n = x.size
+    in_bytes = n * 4
+    nb = 12                                       # 620 MB of inputs in rotation
+    xs = [torch.from_numpy(x).cuda() for _ in range(nb)]
+    ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(nb)]
+    cfg = qp.qp_default_search_cfg()
+    cfg.cands_per_round = 32
+    ws = qp.alloc_workspace(n, cfg)
+    st = qp.qp_stats(xs[0], ws)
+    rot = f"{reps} back-to-back launches over {nb} rotating buffer sets between two HIP events"
+    ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
+    out = {"elements": n, "input": "fp32", "cands_per_round": 32, "buffers_rotated": nb,
+           "roofline_stats": hbm_entry("k_stats_pass1 + k_stats_pass2", 2 * in_bytes, ts, None, None, rot), "per_bitwidth": {}}
+    for b in si.CONFIG_BITS["C3"]:
+        packs = [qp.alloc_packed(n, b) for _ in range(nb)]
+        res, q = qp.qp_dsaciq_search(xs[0], st, b, ws, cfg=cfg)
+        tsr = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], b, ws, cfg=cfg), 24)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % nb]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % nb], q, ys[r % nb]))
+        tsend = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % nb], cfg=cfg), 24)
+        byts = in_bytes + n * b / 8
+        out["per_bitwidth"][str(b)] = {
+            "j_star": res.j_star, "mse_star_over_mse_aciq": res.mse_star / res.mse_aciq,
+            "sender_path_us_per_tensor": tsend,
+            "roofline_search": alu_entry("k_search_mse<fp32,13> (+ k_search_setup)", n, 101, tsr, None,
+                                         "24 back-to-back searches over rotating inputs between two HIP events"),
+            "roofline_pack": hbm_entry(f"k_quant_pack<{b},fp32>", byts, tp, None, None, rot),
+            "roofline_unpack": hbm_entry(f"k_unpack_dequant<{b}>", byts, tu, None, None, rot)}
+        del packs
+    return out
 
 
 def large_tensor_leg(qp, si, torch, timed_reps, reps):
-    """quantize+pack and unpack+dequantize on the 256x577x1024 bf16 tensor (Student-t, df 3, x0.5)."""
+    """C5: statistics, search, quantize+pack and unpack+dequantize on the 256x577x1024 bf16 tensor (Student-t, df 3,
+    x0.5): 302 MB in, larger than the Infinity Cache by itself, so every launch is served by HBM."""
     h = si.make_config("C5")
     n = h.size
     nb = 3
     xs = [torch.from_numpy(h.view("int16").copy()).cuda().view(torch.bfloat16) for _ in range(nb)]
     ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(nb)]
     ws = qp.alloc_workspace(n)
+    # plain device copies of known size: the calibration of FETCH_SIZE / WRITE_SIZE under a counter run
+    for i in range(nb):
+        ys[(i + 1) % nb].copy_(ys[i])
     st = qp.qp_stats(xs[0], ws)
-    out = {"elements": n, "input": "bf16", "buffers_rotated": nb, "stats_us": None}
-    out["stats_us"] = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
-    # a bf16 tensor of this size goes through its value table: one read of the tensor (not two passes)
-    out["stats_GBs"] = n * 2 / out["stats_us"] / 1e3
+    rot = f"{reps} back-to-back launches over {nb} rotating buffer sets between two HIP events"
+    t_stats = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
+    out = {"elements": n, "input": "bf16", "buffers_rotated": nb, "stats_us": t_stats,
+           # a bf16 tensor of this size goes through its value table: ONE read of the tensor (2 B per element) instead of
+           # the two passes (4 B per element) the two-pass statistics need; the rate is quoted on the one read
+           "roofline_stats": hbm_entry("k_value_table_zero + k_value_hist_bf16 + k_stats_from_table (one read of the tensor)",
+                                       n * 2, t_stats, TRAFFIC_RATIO["c5_value_hist"], TRAFFIC_SOURCE["c5"], rot)}
     tcopy = timed_reps(lambda r: ys[(r + 1) % nb].copy_(ys[r % nb]))
     out["hbm_copy_reference_GBs"] = 2 * n * 4 / tcopy / 1e3   # plain device-to-device copy of the fp32 output tensor
+    out["per_bitwidth"] = {}
     for b in si.CONFIG_BITS["C5"]:
         packs = [qp.alloc_packed(n, b) for _ in range(nb)]
         res, q = qp.qp_dsaciq_search(xs[0], st, b, ws)
         tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % nb]))
         tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % nb], q, ys[r % nb]))
-        ts = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], b, ws)) if b == 4 else None
+        ts = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], b, ws))
+        tsend = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % nb]))
         bp, bu = n * 2 + n * b / 8, n * 4 + n * b / 8
-        out[str(b)] = {"pack_us": tp, "pack_GBs": bp / tp / 1e3, "pack_frac_hbm": bp / tp / 1e3 / HBM_PEAK_GBS,
-                       "unpack_us": tu, "unpack_GBs": bu / tu / 1e3, "unpack_frac_hbm": bu / tu / 1e3 / HBM_PEAK_GBS}
-        if ts:
-            out["dsaciq_us_per_tensor"] = ts
-            # the whole sender path (statistics, search, quantize+pack) per tensor, device-resident parameters
-            out["sender_path_us_per_tensor"] = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % nb]))
+        out["per_bitwidth"][str(b)] = {
+            "j_star": res.j_star,
+            # search alone = table zero + value-count pass over the tensor + 101 candidates over the 65536-entry table
+            "dsaciq_us_per_tensor": ts, "sender_path_us_per_tensor": tsend,
+            "roofline_pack": hbm_entry(f"k_quant_pack<{b},bf16>", bp, tp, TRAFFIC_RATIO["c5_pack"], TRAFFIC_SOURCE["c5"], rot),
+            "roofline_unpack": hbm_entry(f"k_unpack_dequant<{b}>", bu, tu, TRAFFIC_RATIO["c5_unpack"], TRAFFIC_SOURCE["c5"], rot)}
         del packs
     return out
 
 
-def c4_stream_leg(qp, si, torch, n_mb=48):
-    """Sender path + receiver per microbatch (32x257x1280 fp32, 42 MB), back to back on one stream, over a ring of
-    eight unit-Laplace buffers scaled per microbatch; the bitwidth of each microbatch follows the seeded bandwidth
-    trace.  All inputs are resident before the timed region."""
+def c4_stream_leg(qp, si, torch, n_mb):
+    """C4: sender path + receiver per microbatch (32x257x1280 fp32, 42 MB), back to back on one stream, over a ring of
+    eight unit-Laplace buffers scaled per microbatch on the device; the bitwidth of each microbatch follows the
+    seeded bandwidth trace.  All n_mb inputs (21 GB at 500) are resident before the timed region."""
     n = si.numel("C4")
     stream = si.c4_stream(n_mb)
     ring = [torch.from_numpy(si.unit_laplace(n, 100 + b)).cuda() for b in range(8)]
-    xs = [ring[buf] * b_m for (buf, b_m, bw, bits) in stream]          # 48 x 42 MB, all distinct
+    xs = [ring[buf] * b_m for (buf, b_m, bw, bits) in stream]          # n_mb x 42 MB, all distinct
     packs = {k: qp.alloc_packed(n, k) for k in sorted({s[3] for s in stream})}
     ws = qp.alloc_workspace(n)
     y = torch.empty(n, dtype=torch.float32, device="cuda")
@@ -336,13 +431,15 @@ def c4_stream_leg(qp, si, torch, n_mb=48):
     hist = {}
     for s_ in stream:
         hist[str(s_[3])] = hist.get(str(s_[3]), 0) + 1
-    return {"elements_per_microbatch": n, "microbatches": n_mb, "bitwidths_used": hist, "us_per_microbatch": us,
+    return {"elements_per_microbatch": n, "microbatches": n_mb, "input_bytes_resident": n_mb * n * 4,
+            "bitwidths_used": hist, "us_per_microbatch": us,
             "activation_GBs": n * 4 / us / 1e3,
             "timed": "statistics, DS-ACIQ (t = 100), quantize+pack, unpack+dequantize per microbatch, one stream, two HIP events"}
 
 
 def small_tensor_leg(qp, si, torch, timed_reps):
-    """Sender path (statistics, DS-ACIQ t = 100, quantize+pack) and its search alone on the 1x197x768 tensor."""
+    """C1: sender path (statistics, DS-ACIQ t = 100, quantize+pack) and its search alone on the 1x197x768 tensor,
+    launched eagerly and replayed from a HIP graph that holds 16 sender paths over rotating inputs."""
     x = si.make_config("C1")
     n = x.size
     nb = 4
@@ -352,25 +449,75 @@ def small_tensor_leg(qp, si, torch, timed_reps):
     qp.qp_stats(xs[0], ws)
     t_search = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], 4, ws))
     t_send = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], 4, ws, packed))
+    # the same 16 sender paths captured once and replayed: what the launch overhead of the five kernels costs
+    per_graph = 16
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        for r in range(per_graph):
+            qp.qp_compress_async(xs[r % nb], 4, ws, packed)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        for r in range(per_graph):
+            qp.qp_compress_async(xs[r % nb], 4, ws, packed)
+    torch.cuda.synchronize()
+    t_graph = timed_reps(lambda r: g.replay(), 16) / per_graph
     return {"elements": n, "bits": 4, "dsaciq_us_per_tensor": t_search, "sender_path_us_per_tensor": t_send,
-            "timed": "back-to-back calls on one stream between two HIP events"}
+            "sender_path_us_per_tensor_graph_replay": t_graph,
+            "timed": "back-to-back calls on one stream between two HIP events; graph: 16 replays of a HIP graph holding 16 sender paths"}
 
 
 def cpu_baseline(x_host, bits_set):
-    """The oracle as it stands (single thread, never tuned), on the first quarter of the tensor."""
+    """The oracle as it stands (never tuned) on the first quarter of the C2 tensor, all six bitwidths: once on a
+    single thread, and once with the timing harness spreading the same calls over the host's cores (the search's
+    candidates over threads; statistics, quantize, pack, unpack and dequantize over contiguous chunks of the tensor
+    whose lengths are multiples of 32 codes).  The oracle's code is the same in both."""
+    from concurrent.futures import ThreadPoolExecutor
+
     from oracle import qp_oracle as orc
     sample = x_host[: x_host.size // 4]
+    n = sample.size
     t0 = time.perf_counter()
     rc, st = orc.stats(sample)
     for b in bits_set:
         res, q, _ = orc.dsaciq_search(sample, st, b, 100)
         codes = orc.quantize(sample, q)
         stream = orc.pack(codes, b)
-        y = orc.dequantize(orc.unpack(stream, sample.size, b), q)
-    dt = time.perf_counter() - t0
-    return {"value": len(bits_set) * sample.size * 4 / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"first quarter of the tensor ({sample.size} elements), all six bitwidths, {dt:.1f} s of CPU time",
-            "seconds": dt}
+        y = orc.dequantize(orc.unpack(stream, n, b), q)
+    dt1 = time.perf_counter() - t0
+
+    ncpu = os.cpu_count() or 1
+    try:
+        ncpu = min(ncpu, len(os.sched_getaffinity(0)))
+    except (AttributeError, OSError):
+        pass
+    threads = max(1, min(16, ncpu))           # the share of a one-GPU box
+    step = ((n + threads - 1) // threads + 31) // 32 * 32
+    chunks = [sample[i:i + step] for i in range(0, n, step)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(orc.stats, chunks))                                  # timing only: per-chunk statistics
+        for b in bits_set:
+            res, q, _ = orc.dsaciq_search_threads(sample, st, b, 100, threads)
+            list(ex.map(lambda c: orc.dequantize(orc.unpack(orc.pack(orc.quantize(c, q), b), c.size, b), q), chunks))
+    dtn = time.perf_counter() - t0
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    work = len(bits_set) * n * 4
+    return {"value": work / dt1 / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first quarter of the C2 tensor ({n} elements), all six bitwidths, {dt1:.1f} s of CPU time",
+            "seconds": dt1,
+            "all_cores": {"value": work / dtn / 1e9, "unit": "GB/s", "cores": threads, "seconds": dtn,
+                          "how": "same oracle calls; the timing harness spreads the search's candidates and contiguous "
+                                 "chunks of the tensor over host threads"},
+            "host": {"cpu_model": model, "os_cpu_count": os.cpu_count(), "usable_cpus": ncpu}}
 
 
 if __name__ == "__main__":
