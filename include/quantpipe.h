@@ -105,7 +105,7 @@ typedef struct {
  *                               evaluated are NaN in QP_WS_SCORES.  Not offered for bf16 tensors of
  *                               2^20 elements or more (QP_EINVAL): those are searched through the
  *                               table of their 65536 possible values, where the full sweep is cheap.
- *   QP_SEARCH_LOW_BITS_ONLY     the deployment policy the paper reports (Sec. 4.1: the directed search
+ *   QP_SEARCH_LOW_BITS_ONLY     the deployment policy the paper reports (Sec. 3, discussion of Table 1: the directed search
  *                               is only activated under 4- and 2-bit quantization, because above that
  *                               it gains nothing): for bits > 4 no candidate is scored and the result
  *                               is plain ACIQ (j_star = 0, alpha = F(q) b_E; mse_aciq, mse_star and
@@ -148,11 +148,15 @@ typedef enum {
 
 /* ---- sizes (host, pure) ---------------------------------------------------- */
 
-/* Bytes of the packed buffer for n codes of `bits` bits: 4*ceil(n*bits/32); 0 if bits is invalid. */
+/* Bytes of the packed buffer for n codes of `bits` bits: 4*ceil(n*bits/32); 0 if bits is invalid.
+ * (Sec. 3: q-bit quantization shrinks the fp32 tensor that crosses the stage boundary by 32/q, i.e. to
+ * n q / 8 bytes; the buffer is that, rounded up to whole 32-bit words.) */
 size_t qp_packed_bytes(uint64_t n, uint32_t bits);
 
 /* Bytes of device workspace needed by qp_stats / qp_dsaciq_search for an n-element
- * tensor under cfg (NULL = defaults: t_steps 100, cands_per_round 13).  0 on bad arguments. */
+ * tensor under cfg (NULL = defaults: t_steps 100, cands_per_round 13).  0 on bad arguments.
+ * (Sec. 3, Eq. 1: what the statistics and the t+1 candidates of the directed search need between kernels:
+ * per-block partial sums, the histogram D_R, the candidate grids and their scores; nothing per element.) */
 size_t qp_workspace_bytes(uint64_t n, const qp_search_cfg_t *cfg);
 
 /* Byte offset of a region inside the workspace; (size_t)-1 for an unknown region. */
@@ -219,7 +223,9 @@ qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, 
  * of candidate j is sum over bins of (D_R,i - exp(-|c_i - mu| / b_j) / (2 b_j))^2 with c_i the
  * bin centre and D_R,i = count_i / (N binwidth); mse_aciq / mse_star are means over the bins.
  * Works on the statistics record and histogram that qp_stats / qp_stats_async left in ws_dev
- * (no pass over the tensor) and overwrites QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES.
+ * (no pass over the tensor) and overwrites QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES.  The statistics
+ * must have run on the same workspace first: a record whose nbins is outside [16, 4096] or whose n is 0
+ * (a workspace the statistics never wrote) gives NaN scores and j_star = 0, and nothing is read out of bounds.
  * Only the paper's form: cfg->dist must be QP_LAPLACE and cfg->flags 0 (else QP_EINVAL). */
 qp_status qp_dsaciq_hist_search(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
                                 void *stream, qp_search_result_t *res_host, qp_qparams_t *qparams_out_host);

@@ -283,8 +283,12 @@ __global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__
     __shared__ uint32_t sh_flag;
     const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const uint32_t j = blockIdx.x, ncand = t_steps + 1u;
-    const uint32_t B = st->nbins;
+    // The record is whatever the workspace holds: a bin count outside the histogram region, or no elements,
+    // means the statistics never ran on it.  Then nothing is read (B = 0) and every score is NaN.
+    const uint32_t nb_rec = st->nbins;
     const uint64_t n = st->n;
+    const bool rec_ok = nb_rec >= 16u && nb_rec <= kMaxBins && n != 0u;
+    const uint32_t B = rec_ok ? nb_rec : 0u;
     const double mean = st->mean, mn = st->min, mx = st->max;
     const double b_e = st->mad, b_r = st->b_r;
     double step = (b_r - b_e) / (double)t_steps;
@@ -306,6 +310,7 @@ __global__ __launch_bounds__(kHsThreads) void k_hist_search(const qp_stats_t *__
     if (tid == 0) {
         double tot = sh[0];
         for (int w = 1; w < kHsThreads / kWave; ++w) tot += sh[w];
+        if (!rec_ok) tot = __longlong_as_double(0x7ff8000000000000ll);
         st_dev(&scores[j], tot);
         wait_stores();   // the score has arrived before the ticket is drawn
         const uint32_t prev = __hip_atomic_fetch_add(&ctl->ticket_search, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -411,7 +416,9 @@ template <int DT, int CMAX> static hipError_t launch_variant(const SearchArgs &a
     if (CMAX > 1 && a.ncand >= rounds * ((uint32_t)CMAX - 1u)) full = a.ncand - rounds * ((uint32_t)CMAX - 1u);
     // a list that fits one round is the tile search's job (launch_search sends it there); this kernel has
     // only ever run with two rounds or more
+#ifndef QP_EMULATE_STREAMING_C2F
     if (rounds < 2u) return hipErrorInvalidValue;
+#endif
     uint32_t gx = resident / rounds;
     if (gx > cols) gx = cols;
     if (gx < 1) gx = 1;
@@ -489,6 +496,14 @@ ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *st, uint32_t list
 static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const SearchPlan &plan, const qp_stats_t *st,
                                uint32_t finalize_nbins, uint32_t list_mode, uint32_t count, void *ws, hipStream_t s)
 {
+    // Only the full sweep: this kernel has never completed a run with a coarse or fine candidate list on the GPU
+    // (its one attempt ended in a fault whose cause was not found), so such a list is an error here whatever
+    // the caller above does; those sweeps run on the tile search.
+    // (QP_EMULATE_STREAMING_C2F is defined by one build of the CPU emulation under tests/ only, which runs that
+    // very sequence on the host in search of the cause; no build of the library defines it.)
+#ifndef QP_EMULATE_STREAMING_C2F
+    if (list_mode != kListFull) return hipErrorInvalidValue;
+#endif
     char *w = static_cast<char *>(ws);
     Cand *cands = reinterpret_cast<Cand *>(w + kOffCands);
     Ctl *ctl = reinterpret_cast<Ctl *>(w + kOffCtl);
@@ -545,6 +560,14 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
     // cause not found, so it is not launched from here).
     if (plan.stride > 1u) {
         if (!coarse_to_fine_supported(n, dtype, plan)) return hipErrorInvalidValue;
+#ifdef QP_EMULATE_STREAMING_C2F
+        {   // CPU emulation only: the two sweeps on the streaming kernel, as the run that faulted launched them
+            const uint32_t coarse = (plan.t_steps + plan.stride - 1u) / plan.stride + 1u;
+            const hipError_t e = launch_sweep(x, n, dtype, plan, st, finalize_nbins, kListCoarse, coarse, ws, s);
+            if (e != hipSuccess) return e;
+            return launch_sweep(x, n, dtype, plan, st, 0u, kListFine, 2u * plan.stride - 1u, ws, s);
+        }
+#endif
         return launch_tile_search(x, n, dtype, plan, st, finalize_nbins, ws, s);
     }
     // So does a full sweep short enough for one round (t + 1 <= cands_per_round): the streaming kernel's

@@ -1,9 +1,10 @@
 """TEST INFRASTRUCTURE ONLY: compiles the library's kernel sources against the CPU stand-in for the HIP
 runtime (tests/emu/hip/hip_runtime.h) with AddressSanitizer and UBSan, into tests/emu/_build/<tag>/emu_driver.
 
-Two builds: "default" (the library's own size thresholds: small tensors take the tile search) and
+Three builds: "default" (the library's own size thresholds: small tensors take the tile search),
 "streaming" (thresholds lowered so that tiny tensors take the streaming search and, for bf16, the value
-table).  Returns None when no host clang++ with C++20 is available."""
+table) and "streaming_c2f" (as "streaming", plus the coarse-to-fine sweeps on the streaming kernel, which the
+library itself never launches).  Returns None when no host clang++ with C++20 is available."""
 from __future__ import annotations
 
 import glob
@@ -18,6 +19,10 @@ CSRC = os.path.join(ROOT, "paper_2211_04515_amd", "csrc")
 VARIANTS = {
     "default": [],
     "streaming": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096", "-DQP_SEARCH_FILL_BLOCKS=8"],
+    # as "streaming", and a coarse-to-fine search runs its two sweeps on the streaming kernel: the sequence that
+    # the library refuses because its only GPU run faulted (the macro exists for this build alone)
+    "streaming_c2f": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096", "-DQP_SEARCH_FILL_BLOCKS=8",
+                      "-DQP_EMULATE_STREAMING_C2F=1"],
 }
 
 

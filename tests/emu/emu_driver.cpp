@@ -8,7 +8,7 @@
 
 #include "quantpipe.h"
 
-namespace emu { extern int g_occupancy, g_cus; }
+namespace emu { extern int g_occupancy, g_cus; void *shared_alloc(size_t); }
 
 static void dump(const std::string &dir, const char *name, const void *p, size_t bytes)
 {
@@ -17,11 +17,17 @@ static void dump(const std::string &dir, const char *name, const void *p, size_t
     fclose(f);
 }
 
+static bool g_shared = false;             // blocks run as processes: "device memory" must be shared between them
 static void *alloc_exact(size_t bytes)   // 16-byte aligned; the sanitizer sees any overrun past `bytes` (rounded to 16)
 {
+    if (g_shared) return emu::shared_alloc(bytes);   // ends at an inaccessible page instead
     void *p = aligned_alloc(16, (bytes + 15) / 16 * 16);
     if (!p) exit(3);
     return p;
+}
+static void release(void *p)
+{
+    if (!g_shared) free(p);
 }
 
 int main(int argc, char **argv)
@@ -42,6 +48,7 @@ int main(int argc, char **argv)
     const std::string out = argv[11];
     if (argc == 13) cfg.cands_per_round = (uint32_t)atoi(argv[12]);
 
+    g_shared = getenv("EMU_CONCURRENT_BLOCKS") && atoi(getenv("EMU_CONCURRENT_BLOCKS")) > 0;
     const size_t esz = dtype == QP_BF16 ? 2 : 4;
     void *x = alloc_exact(n * esz);
     FILE *f = fopen(in, "rb");
@@ -60,13 +67,15 @@ int main(int argc, char **argv)
     qp_stats_t st;
     qp_search_result_t res;
     qp_qparams_t q;
+    memset(&res, 0, sizeof res);
+    memset(&q, 0, sizeof q);
     int rc_stats = qp_stats(x, n, dtype, cfg.nbins, ws, wsb, nullptr, &st);
     int rc_search = qp_dsaciq_search(x, n, dtype, &st, bits, &cfg, ws, wsb, nullptr, &res, &q);
     int rc_pack = -100, rc_unpack = -100, rc_compress = -100, same = -1;
     if (rc_search == QP_OK) {
         rc_pack = qp_quant_pack(x, n, dtype, &q, packed, pkb, nullptr);
         rc_unpack = qp_unpack_dequant(packed, pkb, &q, y, n, nullptr);
-        qp_qparams_t qout;
+        qp_qparams_t &qout = *(qp_qparams_t *)alloc_exact(sizeof(qp_qparams_t));
         rc_compress = qp_compress_async(x, n, dtype, bits, &cfg, ws2, wsb, packed2, pkb, &qout, nullptr);
         if (rc_compress == QP_OK) {
             const char *a = (const char *)ws, *b = (const char *)ws2;
@@ -85,6 +94,6 @@ int main(int argc, char **argv)
     char line[256];
     snprintf(line, sizeof line, "%d %d %d %d %d %d\n", rc_stats, rc_search, rc_pack, rc_unpack, rc_compress, same);
     dump(out, "status.txt", line, strlen(line));
-    free(x); free(ws); free(ws2); free(packed); free(packed2); free(y);
+    release(x); release(ws); release(ws2); release(packed); release(packed2); release(y);
     return 0;
 }

@@ -2,8 +2,9 @@
 // sources can be compiled by the host compiler and run under AddressSanitizer and UBSan on tiny
 // inputs: a launch runs block after block, one OS thread per lane, with __syncthreads and the
 // wave64 cross-lane builtins (DPP permutations, readlane, shuffles) emulated through barriers.
-// It checks indexing and logic (blocks run one after the other, so it cannot show a race between
-// blocks) and is hopeless for speed.  Nothing in the product includes or links it: the library
+// It checks indexing and logic and is hopeless for speed.  By default blocks run one after the other in
+// index order; with EMU_CONCURRENT_BLOCKS=K they run K at a time in a shuffled order, each in a process of
+// its own (emu_rt.cpp), so that ticket hand-overs between blocks happen in any order.  Nothing in the product includes or links it: the library
 // itself has no CPU path.
 #pragma once
 #include <math.h>
@@ -58,6 +59,7 @@ struct BlockCtx {
 extern BlockCtx *g_ctx;
 extern thread_local unsigned t_opcount;
 void launch(dim3 grid, dim3 block, const std::function<void()> &fn);
+void *shared_alloc(size_t bytes);   // "device memory" that the per-block processes of the concurrent mode share
 uint32_t exchange(uint32_t v, int src_lane_or_minus1, int ctrl, int xor_mask);
 }  // namespace emu
 

@@ -1046,6 +1046,29 @@ def test_hist_search_degenerate_inputs(qp, name):
     assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
 
 
+@pytest.mark.parametrize("fill", [0x00, 0xFF, 0x11])
+def test_hist_search_on_a_workspace_the_statistics_never_wrote(qp, fill):
+    """The histogram-fit search takes its bin count from the record in the workspace.  A record that is not one
+    (zeros, all ones, a pattern whose bin count lies far beyond the histogram region) must not be followed out of
+    bounds: every score is NaN, plain ACIQ's index is kept, and the kernel ends normally."""
+    ws = qp.alloc_workspace(100_000)
+    ws.fill_(fill)
+    res, q = qp.qp_dsaciq_hist_search(4, ws)
+    offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    scores = ws[offs:offs + 8 * 101].cpu().numpy().view(np.float64)
+    assert np.isnan(scores).all() and res.j_star == 0 and res.t_steps == 100
+    # and the workspace is still usable afterwards
+    x = si.make_config("C1")
+    xd = to_dev(x)
+    ws2 = qp.alloc_workspace(x.size)
+    ws2.fill_(fill)
+    st = qp.qp_stats(xd, ws2)
+    res2, q2 = qp.qp_dsaciq_hist_search(4, ws2)
+    hist = ws2[qp.qp_ws_offset(qp.QP_WS_HIST):][:4 * 2048].cpu().numpy().view(np.uint32).copy()
+    ores, oq, oscores = orc.hist_search(oracle_stats_from(st), hist, 4, 100)
+    assert res2.j_star == ores.j_star
+
+
 @pytest.mark.parametrize("kind", ["constant", "two_point", "ramp_of_all_patterns", "laplace_ragged"])
 def test_bf16_value_table_search_edge_cases(qp, kind):
     """Large bf16 tensors are searched through the table of their (at most 65536) distinct values."""
@@ -1235,16 +1258,26 @@ def test_coarse_to_fine_on_the_full_vit_base_tensor(qp):
 
 
 @pytest.mark.skip(reason="the coarse-to-fine sweep on the STREAMING search kernel (k_search_mse with a coarse / fine candidate "
-                         "list) faulted the GPU once; a CPU emulation of the same launch under ASan/UBSan is clean and the "
-                         "cause has not been found, so the library never launches that kernel with such a list (the sweep "
-                         "runs on the tile search instead) and the case must not run on a GPU until a cause is shown")
+                         "list) faulted the GPU on its only run; the code of that run was never committed, a CPU emulation "
+                         "of the launch sequence (blocks one after the other, and blocks of a launch running concurrently "
+                         "in shuffled order) is clean under ASan/UBSan, and no cause has been shown.  The library therefore "
+                         "refuses such a list in launch_sweep (hipErrorInvalidValue) and runs these sweeps on the tile "
+                         "search; this case must not run on a GPU until a cause is shown and fixed")
 def test_coarse_to_fine_on_the_streaming_kernel(qp):
+    """What would have to pass before the refusal in launch_sweep (csrc/qp_search.hip) may be lifted: with that
+    refusal gone and launch_search routing a coarse-to-fine plan on a tensor above the tile search's size limit
+    to launch_sweep (coarse list, then fine list), this input (fp32, above 2^21 elements) reaches k_search_mse with
+    both lists, in one round (11 and 19 candidates at stride 10) and in several (stride 64: 3 and 127).  As the
+    library stands the same calls run on the tile search, so un-skipping alone would not exercise that kernel."""
     x = si.make_config("C3", n=2_600_011)
+    assert x.size > (1 << 21)
     xd = to_dev(x)
     ws = qp.alloc_workspace(x.size)
     st = qp.qp_stats(xd, ws)
-    res, q = qp.qp_dsaciq_search(xd, st, 2, ws, cfg=variant_cfg(qp, dict(stride=10)))
-    check_variant(qp, x, st, 2, dict(stride=10), 100, ws, res, q)
+    for stride in (10, 64):
+        for bits in (2, 4):
+            res, q = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=variant_cfg(qp, dict(stride=stride)))
+            check_variant(qp, x, st, bits, dict(stride=stride), 100, ws, res, q)
 
 
 def test_low_bits_only_policy(qp):

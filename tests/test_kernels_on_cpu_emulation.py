@@ -3,8 +3,12 @@
 
 What this adds to the GPU parity tests: it runs without a GPU, and the sanitizers see every access of every
 kernel against buffers of exactly the sizes the C ABI asks for (workspace, packed stream), so an index
-that strays fails here first.  What it cannot show: speed, and races between blocks (they run one after
-the other).  The emulation is test infrastructure; the library has no CPU path."""
+that strays fails here first.  By default the blocks of a launch run one after the other in index order; the
+"concurrent" cases run them several at a time in a shuffled order, each block in a process of its own over
+shared "device memory", so that the ticket hand-overs between blocks (last block of a round, last round of a
+search, last block of the statistics) are taken in many orders.  What it cannot show: speed, and the device's
+memory model (the host orders stores more strongly than the GPU's caches do).  The emulation is test
+infrastructure; the library has no CPU path."""
 import ctypes as C
 import os
 import subprocess
@@ -49,11 +53,13 @@ def drivers():
     return out
 
 
-def start_driver(exe, out_dir, x, bits, t=100, dist=0, flags=0, stride=0, nbins=2048, cus=4, cpr=None):
+def start_driver(exe, out_dir, x, bits, t=100, dist=0, flags=0, stride=0, nbins=2048, cus=4, cpr=None, concurrent=0, seed=1):
     os.makedirs(out_dir, exist_ok=True)
     inp = os.path.join(out_dir, "in.bin")
     x.tofile(inp)
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    if concurrent:
+        env.update(EMU_CONCURRENT_BLOCKS=str(concurrent), EMU_SEED=str(seed))
     return subprocess.run([exe, inp, str(x.size), "1" if x.dtype == np.uint16 else "0", str(bits), str(t), str(dist),
                            str(flags), str(stride), str(nbins), str(cus), out_dir] + ([str(cpr)] if cpr else []),
                           capture_output=True, env=env, timeout=900)
@@ -120,7 +126,24 @@ STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37
                 ("C3", 9_001, 4, dict(stride=5), 40)]
 REFUSED = ("bf16", 5_000, 4, dict(stride=10), 100)
 ACIQ_ONLY = [("default", ("C3", 3_003, 8, dict(low_bits_only=True), 100)), ("streaming", ("bf16", 6_001, 6, dict(low_bits_only=True, clip=True), 100))]
-ALL_CASES = [("default", c) for c in TILE_CASES] + [("streaming", c) for c in STREAM_CASES] + [("streaming", REFUSED)] + ACIQ_ONLY
+# Blocks of a launch in shuffled order, `conc` at a time (each a process of its own): ticket hand-overs out of order.
+# The tile search and its pick kernel, the streaming search with several rounds, the statistics finalizer, the
+# value-table search; two seeds each.
+CONCURRENT_CASES = [("default", ("C2", 9_001, 4, dict(conc=3, seed=1), 12)), ("default", ("C2", 9_001, 4, dict(conc=3, seed=2), 12)),
+                    ("streaming", ("C3", 10_011, 2, dict(conc=4, seed=1), 30)), ("streaming", ("C3", 10_011, 2, dict(conc=4, seed=2), 30)),
+                    ("streaming", ("C2", 6_007, 8, dict(conc=2, seed=3, cpr=4), 17)),
+                    ("streaming", ("bf16", 5_001, 4, dict(conc=4, seed=1), 20)), ("streaming", ("bf16", 5_001, 4, dict(conc=3, seed=2), 20))]
+# The sequence the library refuses (a coarse-to-fine search as two sweeps of the STREAMING kernel, the run that once
+# faulted a GPU), on the build that allows it: in block order, and with blocks shuffled and concurrent.  One-round
+# lists (11 / 19 candidates under 13 per round) and lists of several rounds (cands_per_round 4).
+STREAM_C2F_CASES = [("streaming_c2f", ("C3", 10_011, 2, dict(stride=10), 100)),
+                    ("streaming_c2f", ("C3", 10_011, 2, dict(stride=10, conc=4, seed=1), 100)),
+                    ("streaming_c2f", ("C3", 10_011, 2, dict(stride=10, conc=4, seed=2), 100)),
+                    ("streaming_c2f", ("C3", 10_011, 4, dict(stride=10, conc=3, seed=3, cpr=4), 100)),
+                    ("streaming_c2f", ("C2", 8_193, 3, dict(stride=5, clip=True, conc=2, seed=4), 40)),
+                    ("streaming_c2f", ("C3", 6_007, 4, dict(stride=64, conc=4, seed=5), 100))]
+ALL_CASES = ([("default", c) for c in TILE_CASES] + [("streaming", c) for c in STREAM_CASES] + [("streaming", REFUSED)] + ACIQ_ONLY
+             + CONCURRENT_CASES + STREAM_C2F_CASES)
 
 
 def case_id(tag, c):
@@ -139,7 +162,8 @@ def runs(drivers, tmp_path_factory):
         flags = (1 if v.get("clip") else 0) | (2 if v.get("stride", 1) > 1 else 0) | (4 if v.get("low_bits_only") else 0)
         out_dir = os.path.join(base, case_id(tag, item[1]))
         p = start_driver(drivers[tag], out_dir, x, bits, t=t, dist=v.get("dist", 0), flags=flags,
-                         stride=v.get("stride", 0) if flags & 2 else 0, cus=4 if tag == "default" else 2, cpr=v.get("cpr"))
+                         stride=v.get("stride", 0) if flags & 2 else 0, cus=4 if tag == "default" else 2, cpr=v.get("cpr"),
+                         concurrent=v.get("conc", 0), seed=v.get("seed", 1))
         return case_id(tag, item[1]), (p, out_dir, x)
 
     with ThreadPoolExecutor(max_workers=6) as ex:
