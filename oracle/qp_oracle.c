@@ -601,6 +601,39 @@ int orc_dsaciq_search_variant(const float *x, uint64_t n, const orc_stats_t *st,
     return 0;
 }
 
+/* ---- Which model fits the tensor: Laplace or Gaussian (beyond the paper's method) -------------
+ *
+ * The paper takes the Laplace model for granted ("ACIQ assumes the activation follows a Laplace
+ * distribution", Sec. 3); the ACIQ method it builds on also has a Gaussian form.  This picks one per
+ * tensor with the measure Eq. 1 itself uses, the squared distance between the real distribution D_R
+ * (the histogram as a density at the bin centres c_i, D_R,i = count_i / (N binwidth)) and the estimated
+ * one D_E at its moment estimates:
+ *     fit_L = sum_i (D_R,i - exp(-|c_i - mu| / b_E) / (2 b_E))^2,                b_E = MAD,
+ *     fit_G = sum_i (D_R,i - exp(-(c_i - mu)^2 / (2 s^2)) / (s sqrt(2 pi)))^2,   s = sqrt(var).
+ * Gaussian is chosen only if fit_G is strictly below fit_L; a fit that is not a number (one distinct
+ * value, zero scale) never wins, so the paper's model is the default.  Returns ORC_LAPLACE or ORC_GAUSS.
+ */
+int orc_model_fit(const orc_stats_t *st, const uint32_t *hist, double *fit_laplace, double *fit_gauss)
+{
+    const uint32_t B = st->nbins;
+    double binw = (st->max - st->min) / (double)B;
+    double b = st->mad, sg = sqrt(st->var);
+    double fl = 0.0, fg = 0.0;
+    for (uint32_t i = 0; i < B; ++i) {
+        double c = st->min + ((double)i + 0.5) * binw;
+        double d_r = (double)hist[i] / ((double)st->n * binw);
+        double z = c - st->mean;
+        double d_l = exp(-fabs(z) / b) / (2.0 * b);
+        double d_g = exp(-(z * z) / (2.0 * sg * sg)) / (sg * sqrt(2.0 * 3.14159265358979323846));
+        fl += (d_r - d_l) * (d_r - d_l);
+        fg += (d_r - d_g) * (d_r - d_g);
+    }
+    if (B == 0 || st->n == 0) fl = fg = NAN;
+    if (fit_laplace) *fit_laplace = fl;
+    if (fit_gauss) *fit_gauss = fg;
+    return (fg < fl) ? ORC_GAUSS : ORC_LAPLACE;    /* false whenever either is NaN */
+}
+
 /* ---- Adaptive PDA controller: window averages feeding Eq. 2 (Sec. 3 "Adaptive PDA", Sec. 4.2) ----
  * The runtime measures over a window of microbatches (50 in the paper's run) and decides when the
  * window expires, from the window's averages: the bandwidth is what the link carried in the window,

@@ -112,6 +112,8 @@ def lib():
         L.orc_dsaciq_search_variant.argtypes = [fp, C.c_uint64, C.POINTER(Stats), C.c_uint32, C.c_uint32, C.c_int, C.c_int,
                                                 C.c_uint32, C.POINTER(SearchResult), C.POINTER(QParams), dp]
         L.orc_dsaciq_search_variant.restype = C.c_int
+        L.orc_model_fit.argtypes = [C.POINTER(Stats), u32p, dp, dp]
+        L.orc_model_fit.restype = C.c_int
         _lib = L
     return _lib
 
@@ -329,6 +331,16 @@ def dsaciq_search_variant(x, st, bits, t_steps=100, dist=LAPLACE, clip_to_data=F
     if rc:
         raise ValueError("orc_dsaciq_search_variant: bad argument")
     return res, q, scores
+
+
+def model_fit(st, hist):
+    """Which model the histogram fits better.  Returns (LAPLACE or GAUSS, fit_laplace, fit_gauss)."""
+    h, p = _u32(hist)
+    if h.size < st.nbins:
+        raise ValueError("histogram shorter than st.nbins")
+    fl, fg = C.c_double(), C.c_double()
+    d = lib().orc_model_fit(C.byref(st), p, C.byref(fl), C.byref(fg))
+    return d, fl.value, fg.value
 
 
 # ---- adaptive PDA controller (window averages feeding Eq. 2) --------------------------------------

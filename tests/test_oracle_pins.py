@@ -772,3 +772,72 @@ def test_threaded_search_harness_is_the_sequential_search():
     assert res.j_star == 1 and res.mse_aciq == 5.0 / 1000 and res.mse_star == 3.0 / 1000
     res, q = orc.search_pick(st, 4, 2, 1000, [1.0, 1.0, 1.0])
     assert res.j_star == 0
+
+
+# ----------------------------------------------------------------------------- which model fits: Laplace or Gaussian
+
+def _exact_normal_histogram(mu, sigma, lo, hi, nbins, n):
+    edges = np.linspace(lo, hi, nbins + 1)
+    mass = np.diff(scipy.special.ndtr((edges - mu) / sigma))
+    return np.round(mass / mass.sum() * n).astype(np.uint32)
+
+
+def _stats_of_histogram(hist, lo, hi, mu, mad, var):
+    st = orc.Stats()
+    st.n, st.nbins, st.min, st.max = int(hist.sum()), hist.size, lo, hi
+    st.mean, st.mad, st.var = mu, mad, var
+    return st
+
+
+def test_model_fit_picks_the_model_a_histogram_was_drawn_from():
+    """A histogram taken from the Laplace cdf, with the Laplace moments (MAD = b, var = 2 b^2), must fit the Laplace
+    pdf better than the normal pdf of the same variance, and the other way round for one taken from the normal
+    cdf (MAD = sigma sqrt(2/pi), var = sigma^2): in each case the own model's misfit is only the binning error."""
+    n, nbins = 40_000_000, 2048
+    for mu, s in ((0.0, 1.0), (0.3, 0.7), (-2.0, 0.05)):
+        h = _exact_laplace_histogram(mu, s, mu - 12 * s, mu + 12 * s, nbins, n)
+        d, fl, fg = orc.model_fit(_stats_of_histogram(h, mu - 12 * s, mu + 12 * s, mu, s, 2 * s * s), h)
+        assert d == orc.LAPLACE and fl < 1e-3 * fg
+        h = _exact_normal_histogram(mu, s, mu - 8 * s, mu + 8 * s, nbins, n)
+        d, fl, fg = orc.model_fit(_stats_of_histogram(h, mu - 8 * s, mu + 8 * s, mu, s * math.sqrt(2 / math.pi), s * s), h)
+        assert d == orc.GAUSS and fg < 1e-3 * fl
+
+
+@pytest.mark.parametrize("name,expect", [("C1", 0), ("C3", None), ("gauss", 1), ("laplace", 0), ("C5", None)])
+def test_model_fit_matches_independent_numpy_statement(name, expect):
+    if name == "gauss":
+        x = (np.random.default_rng(11).standard_normal(300_000) * 0.6 + 0.2).astype(np.float32)
+    elif name == "laplace":
+        x = np.random.default_rng(12).laplace(-0.1, 0.4, size=300_000).astype(np.float32)
+    elif name == "C5":
+        x = orc.widen_bf16(si.make_config("C5", n=300_000))
+    else:
+        x = si.make_config(name, n=300_000)
+    for nbins in (2048, 64):
+        rc, st, hist = orc.stats(x, nbins=nbins, want_hist=True)
+        d, fl, fg = orc.model_fit(st, hist)
+        binw = (st.max - st.min) / nbins
+        c = st.min + (np.arange(nbins) + 0.5) * binw
+        d_r = hist[:nbins].astype(np.float64) / (st.n * binw)
+        sg = math.sqrt(st.var)
+        ref_l = float(np.sum((d_r - np.exp(-np.abs(c - st.mean) / st.mad) / (2 * st.mad)) ** 2))
+        ref_g = float(np.sum((d_r - np.exp(-((c - st.mean) ** 2) / (2 * sg * sg)) / (sg * math.sqrt(2 * math.pi))) ** 2))
+        assert fl == pytest.approx(ref_l, rel=1e-12) and fg == pytest.approx(ref_g, rel=1e-12)
+        assert d == (orc.GAUSS if ref_g < ref_l else orc.LAPLACE)
+        if expect is not None and nbins == 2048:
+            assert d == expect
+    # the Laplace fit is the histogram-fit search's score of its first candidate (same D_R, same pdf at b_E)
+    rc, st, hist = orc.stats(x, want_hist=True)
+    res, q, scores = orc.hist_search(st, hist, 4, 10)
+    assert orc.model_fit(st, hist)[1] == pytest.approx(scores[0], rel=1e-13)
+
+
+def test_model_fit_degenerate_inputs_keep_the_papers_model():
+    for x in (np.full(500, 2.5, np.float32), np.zeros(10, np.float32), np.array([1.0], np.float32)):
+        rc, st, hist = orc.stats(x, want_hist=True)
+        d, fl, fg = orc.model_fit(st, hist)
+        assert d == orc.LAPLACE and not (fg < fl)
+    # an exact tie keeps Laplace: only a strictly better Gaussian fit switches the model
+    st = orc.Stats()
+    st.n, st.nbins, st.min, st.max, st.mean, st.mad, st.var = 0, 16, 0.0, 1.0, 0.5, 0.2, 0.1
+    assert orc.model_fit(st, np.zeros(16, np.uint32))[0] == orc.LAPLACE
