@@ -58,7 +58,7 @@ extern "C" {
 
 typedef enum { QP_OK = 0, QP_EINVAL = -1, QP_ENOSPC = -2, QP_EHIP = -3, QP_ENONFINITE = -4 } qp_status;
 typedef enum { QP_F32 = 0, QP_BF16 = 1 } qp_dtype;
-typedef enum { QP_LAPLACE = 0, QP_GAUSS = 1 } qp_dist;
+typedef enum { QP_LAPLACE = 0, QP_GAUSS = 1, QP_DIST_AUTO = 2 } qp_dist;
 
 /* Per-tensor statistics (Sec. 3: the activation is modelled as Laplace L(mu, b)). */
 typedef struct {
@@ -93,6 +93,11 @@ typedef struct {
  *                               estimate sigma_E = sqrt(var), alpha = G(q) sigma, search bound
  *                               sigma_R = 1 / (sqrt(2 pi) max(D_R)) (the sigma whose density peak
  *                               equals the histogram's);
+ *   dist = QP_DIST_AUTO         the model is chosen per tensor on the device, with no host round trip: the one whose
+ *                               pdf at its moment estimates lies closer to the histogram D_R (see qp_model_fit);
+ *                               Gaussian only if strictly closer.  The statistics record and histogram that
+ *                               qp_stats / qp_stats_async left in the same workspace are what is judged (and what
+ *                               the grid is then built from); QP_WS_MODEL tells which model was taken;
  *   QP_SEARCH_CLIP_TO_DATA      every candidate range is intersected with the data's own range,
  *                               [max(mu - alpha, min), min(mu + alpha, max)], so one-sided data
  *                               (after a GELU) spends no levels below its minimum;
@@ -121,7 +126,7 @@ typedef struct {
                                   101 candidates in five rounds of 13 and three of 12, which leaves seven
                                   waves per SIMD of gfx950 */
     uint32_t nbins;            /* kept with the configuration for callers; the search itself does not use it */
-    uint32_t dist;             /* QP_LAPLACE (the paper's model) or QP_GAUSS */
+    uint32_t dist;             /* QP_LAPLACE (the paper's model), QP_GAUSS or QP_DIST_AUTO */
     uint32_t flags;            /* QP_SEARCH_* bits, 0 = the paper's method */
     uint32_t coarse_stride;    /* see QP_SEARCH_COARSE_TO_FINE */
 } qp_search_cfg_t;
@@ -143,7 +148,8 @@ typedef enum {
     QP_WS_QPARAMS = 2,   /* qp_qparams_t of the search winner */
     QP_WS_HIST = 3,      /* uint32_t[nbins] */
     QP_WS_CANDS = 4,     /* per candidate {float lo, hi, scale, inv_scale} */
-    QP_WS_SCORES = 5     /* double[t_steps + 1]: sums of squared errors */
+    QP_WS_SCORES = 5,    /* double[t_steps + 1]: sums of squared errors */
+    QP_WS_MODEL = 6      /* qp_model_fit_t: written by qp_model_fit and by a search with dist = QP_DIST_AUTO */
 } qp_ws_region;
 
 /* ---- sizes (host, pure) ---------------------------------------------------- */
@@ -178,7 +184,8 @@ qp_status qp_stats_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t
 /* ---- step 2a: ACIQ threshold (Sec. 3: alpha = F(q) * b) -- host only, pure ----
  * Laplace: alpha = W0(3 * 4^bits) * stats->mad, W0 the principal Lambert W (the
  * stationary point of ACIQ's clipping + rounding noise model).  Gaussian:
- * alpha = G(bits) * sqrt(stats->var) with G from the matching Gaussian noise model. */
+ * alpha = G(bits) * sqrt(stats->var) with G from the matching Gaussian noise model.
+ * QP_DIST_AUTO is not accepted here (QP_EINVAL): the choice needs the histogram, which the host does not hold. */
 qp_status qp_aciq_alpha(const qp_stats_t *stats, uint32_t bits, qp_dist dist, double *alpha_out);
 
 /* The constant alone: F(bits) for QP_LAPLACE, G(bits) for QP_GAUSS; NaN on bad arguments. */
@@ -216,6 +223,23 @@ qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const 
 qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
                                  const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes, void *stream);
 
+/* ---- which model fits the tensor (beyond the paper, which assumes Laplace: Sec. 3) ----------
+ * The measure is Eq. 1's own, the squared distance between the real distribution D_R (the histogram as a
+ * density at the bin centres c_i, D_R,i = count_i / (N binwidth)) and the estimated one at its moment estimates:
+ *     fit_laplace = sum_i (D_R,i - exp(-|c_i - mu| / b_E) / (2 b_E))^2,                        b_E = mad,
+ *     fit_gauss   = sum_i (D_R,i - exp(-(c_i - mu)^2 / (2 sigma^2)) / (sigma sqrt(2 pi)))^2,   sigma = sqrt(var).
+ * dist = QP_GAUSS only if fit_gauss < fit_laplace (a fit that is not a number never wins, so degenerate tensors
+ * keep the paper's model).  Works on the record and histogram that qp_stats / qp_stats_async left in ws_dev (no
+ * pass over the tensor; a record that is not one gives NaN fits and QP_LAPLACE) and leaves the result at
+ * QP_WS_MODEL, where a search with cfg->dist = QP_DIST_AUTO leaves its own. */
+typedef struct {
+    double   fit_laplace, fit_gauss;
+    uint32_t dist;             /* QP_LAPLACE or QP_GAUSS */
+    uint32_t reserved;         /* written as 0 */
+} qp_model_fit_t;
+qp_status qp_model_fit(void *ws_dev, size_t ws_bytes, void *stream, qp_model_fit_t *out_host);
+qp_status qp_model_fit_async(void *ws_dev, size_t ws_bytes, void *stream);
+
 /* ---- step 2b, the other reading of Eq. 1: fit the estimated distribution to the histogram ----
  * Eq. 1 as printed minimises MSE(D_R, D_E) between the real distribution D_R (the histogram of
  * the tensor, as a density) and the estimated one D_E (the Laplace pdf with scale b) over
@@ -224,8 +248,9 @@ qp_status qp_dsaciq_search_async(const void *x_dev, uint64_t n, qp_dtype dtype, 
  * bin centre and D_R,i = count_i / (N binwidth); mse_aciq / mse_star are means over the bins.
  * Works on the statistics record and histogram that qp_stats / qp_stats_async left in ws_dev
  * (no pass over the tensor) and overwrites QP_WS_RESULT / QP_WS_QPARAMS / QP_WS_SCORES.  The statistics
- * must have run on the same workspace first: a record whose nbins is outside [16, 4096] or whose n is 0
- * (a workspace the statistics never wrote) gives NaN scores and j_star = 0, and nothing is read out of bounds.
+ * must have run on the same workspace first (they also clear the ticket that tells the last block to write the
+ * result).  A record whose nbins is outside [16, 4096] or whose n is 0 (a workspace the statistics never wrote)
+ * gives NaN scores, and nothing is read out of bounds; the result record is then not meaningful.
  * Only the paper's form: cfg->dist must be QP_LAPLACE and cfg->flags 0 (else QP_EINVAL). */
 qp_status qp_dsaciq_hist_search(uint32_t bits, const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
                                 void *stream, qp_search_result_t *res_host, qp_qparams_t *qparams_out_host);

@@ -12,7 +12,7 @@ import os
 import torch  # noqa: F401  (must precede CDLL: one HIP runtime per process)
 
 __all__ = [
-    "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS",
+    "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS", "QP_DIST_AUTO", "QP_WS_MODEL", "qp_model_fit_t", "qp_model_fit", "qp_model_fit_async",
     "QP_SEARCH_CLIP_TO_DATA", "QP_SEARCH_COARSE_TO_FINE", "QP_SEARCH_LOW_BITS_ONLY",
     "QP_WS_STATS", "QP_WS_RESULT", "QP_WS_QPARAMS", "QP_WS_HIST", "QP_WS_CANDS", "QP_WS_SCORES",
     "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "qp_controller_t", "QuantPipeError", "BITS",
@@ -24,9 +24,9 @@ __all__ = [
 
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
 QP_F32, QP_BF16 = 0, 1
-QP_LAPLACE, QP_GAUSS = 0, 1
+QP_LAPLACE, QP_GAUSS, QP_DIST_AUTO = 0, 1, 2
 QP_SEARCH_CLIP_TO_DATA, QP_SEARCH_COARSE_TO_FINE, QP_SEARCH_LOW_BITS_ONLY = 1, 2, 4
-QP_WS_STATS, QP_WS_RESULT, QP_WS_QPARAMS, QP_WS_HIST, QP_WS_CANDS, QP_WS_SCORES = range(6)
+QP_WS_STATS, QP_WS_RESULT, QP_WS_QPARAMS, QP_WS_HIST, QP_WS_CANDS, QP_WS_SCORES, QP_WS_MODEL = range(7)
 BITS = (2, 3, 4, 6, 8, 16)
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libquantpipe.so")
@@ -58,6 +58,10 @@ class qp_search_result_t(C.Structure):
     _fields_ = [("b_e", C.c_double), ("b_r", C.c_double), ("b_star", C.c_double), ("alpha_star", C.c_double),
                 ("mse_aciq", C.c_double), ("mse_star", C.c_double), ("j_star", C.c_uint32),
                 ("t_steps", C.c_uint32)]
+
+
+class qp_model_fit_t(C.Structure):
+    _fields_ = [("fit_laplace", C.c_double), ("fit_gauss", C.c_double), ("dist", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class QuantPipeError(RuntimeError):
@@ -93,6 +97,8 @@ def lib():
             "qp_dsaciq_search": (i32, [vp, u64, i32, C.POINTER(qp_stats_t), u32, C.POINTER(qp_search_cfg_t), vp, sz,
                                        vp, C.POINTER(qp_search_result_t), C.POINTER(qp_qparams_t)]),
             "qp_dsaciq_search_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp]),
+            "qp_model_fit": (i32, [vp, sz, vp, C.POINTER(qp_model_fit_t)]),
+            "qp_model_fit_async": (i32, [vp, sz, vp]),
             "qp_dsaciq_hist_search": (i32, [u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, C.POINTER(qp_search_result_t),
                                             C.POINTER(qp_qparams_t)]),
             "qp_dsaciq_hist_search_async": (i32, [u32, C.POINTER(qp_search_cfg_t), vp, sz, vp]),
@@ -117,7 +123,7 @@ def lib():
 
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
            "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
-           "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
+           "qp_dsaciq_search_async", "qp_model_fit", "qp_model_fit_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
            "qp_unpack_dequant_dev", "qp_compress_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update",
            "qp_strerror")
 
@@ -304,6 +310,17 @@ def qp_controller_update(c: qp_controller_t, payload_bits: float, seconds: float
     out = C.c_uint32()
     _check(lib().qp_controller_update(C.byref(c), float(payload_bits), float(seconds), C.byref(out)), "qp_controller_update")
     return out.value
+
+
+def qp_model_fit(ws, stream=None) -> qp_model_fit_t:
+    """Which model (Laplace or Gaussian) the statistics and histogram left in ws fit better."""
+    out = qp_model_fit_t()
+    _check(lib().qp_model_fit(_dev(ws), ws.numel(), _stream(stream), C.byref(out)), "qp_model_fit")
+    return out
+
+
+def qp_model_fit_async(ws, stream=None) -> None:
+    _check(lib().qp_model_fit_async(_dev(ws), ws.numel(), _stream(stream)), "qp_model_fit_async")
 
 
 def qp_dsaciq_hist_search(bits: int, ws, cfg=None, stream=None):

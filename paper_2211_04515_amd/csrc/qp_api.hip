@@ -66,7 +66,7 @@ qp_status check_cfg(const qp_search_cfg_t *cfg)
     if (!cfg) return QP_OK;
     if (cfg->t_steps < 1 || cfg->t_steps > kMaxT) return QP_EINVAL;
     if (cfg->cands_per_round < 1 || cfg->cands_per_round > kMaxCandsPerRound) return QP_EINVAL;
-    if (cfg->dist != QP_LAPLACE && cfg->dist != QP_GAUSS) return QP_EINVAL;
+    if (cfg->dist != QP_LAPLACE && cfg->dist != QP_GAUSS && cfg->dist != QP_DIST_AUTO) return QP_EINVAL;
     if (cfg->flags & ~(QP_SEARCH_CLIP_TO_DATA | QP_SEARCH_COARSE_TO_FINE | QP_SEARCH_LOW_BITS_ONLY)) return QP_EINVAL;
     if (cfg->coarse_stride > 64u) return QP_EINVAL;
     return QP_OK;
@@ -81,6 +81,7 @@ SearchPlan make_plan(uint32_t bits, const qp_search_cfg_t *cfg)
     p.cpr = cfg ? cfg->cands_per_round : 13u;
     p.dist = cfg ? cfg->dist : (uint32_t)QP_LAPLACE;
     p.C = p.dist == QP_GAUSS ? gauss_constant(bits) : laplace_constant(bits);
+    p.C_alt = p.dist == QP_DIST_AUTO ? gauss_constant(bits) : 0.0;
     p.clip = (cfg && (cfg->flags & QP_SEARCH_CLIP_TO_DATA)) ? 1u : 0u;
     p.stride = 1u;
     if (cfg && (cfg->flags & QP_SEARCH_COARSE_TO_FINE)) p.stride = cfg->coarse_stride ? cfg->coarse_stride : 10u;
@@ -158,6 +159,7 @@ size_t qp_ws_offset(qp_ws_region region)
         case QP_WS_HIST: return kOffHist;
         case QP_WS_CANDS: return kOffCands;
         case QP_WS_SCORES: return kOffScores;
+        case QP_WS_MODEL: return kOffModel;
         default: return (size_t)-1;
     }
 }
@@ -234,6 +236,11 @@ static qp_status search_common(const void *x_dev, uint64_t n, qp_dtype dtype, co
     if (w != QP_OK) return w;
     const SearchPlan plan = make_plan(bits, cfg);
     if (!plan.aciq_only && plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;   // see quantpipe.h
+    if (plan.dist == QP_DIST_AUTO) {   // the choice of the model, on the record and histogram in the workspace
+        if (finalize_nbins) return QP_EINVAL;   // (internal: the record must already be final)
+        const qp_status m = hip_status(launch_model_fit(ws_dev, static_cast<hipStream_t>(stream)));
+        if (m != QP_OK) return m;
+    }
     return hip_status(launch_search(x_dev, n, dtype, plan, stats, finalize_nbins, value_table_ready, ws_dev,
                                     static_cast<hipStream_t>(stream)));
 }
@@ -258,6 +265,26 @@ qp_status qp_dsaciq_search(const void *x_dev, uint64_t n, qp_dtype dtype, const 
         return QP_EHIP;
     if (qparams_out_host &&
         hipMemcpyAsync(qparams_out_host, w + kOffQParams, sizeof(qp_qparams_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return QP_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return QP_EHIP;
+    return QP_OK;
+}
+
+qp_status qp_model_fit_async(void *ws_dev, size_t ws_bytes, void *stream)
+{
+    if (!ws_dev || !aligned16(ws_dev)) return QP_EINVAL;
+    if (ws_bytes < kOffSearchPart) return QP_ENOSPC;   // only the fixed-size head of the workspace is used
+    return hip_status(launch_model_fit(ws_dev, static_cast<hipStream_t>(stream)));
+}
+
+qp_status qp_model_fit(void *ws_dev, size_t ws_bytes, void *stream, qp_model_fit_t *out_host)
+{
+    if (!out_host) return QP_EINVAL;
+    const qp_status st = qp_model_fit_async(ws_dev, ws_bytes, stream);
+    if (st != QP_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(out_host, static_cast<char *>(ws_dev) + kOffModel, sizeof(qp_model_fit_t), hipMemcpyDeviceToHost,
+                       s) != hipSuccess)
         return QP_EHIP;
     if (hipStreamSynchronize(s) != hipSuccess) return QP_EHIP;
     return QP_OK;
@@ -356,10 +383,12 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     }
     // The two statistics passes leave partials and the search finalizes them itself; a large bf16 tensor goes
     // through its value table instead, which the statistics build and finalize and the search then reuses.
+    // (With the model chosen on the device the record is needed before the search starts: the statistics finalize it.)
     const bool table = uses_value_table(n, dtype);
-    st = hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), false));
+    const bool final_record = table || (cfg && cfg->dist == QP_DIST_AUTO);
+    st = hip_status(launch_stats(x_dev, n, dtype, nbins, ws_dev, static_cast<hipStream_t>(stream), final_record));
     if (st != QP_OK) return st;
-    st = search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream, table ? 0u : nbins, table);
+    st = search_common(x_dev, n, dtype, nullptr, bits, cfg, ws_dev, ws_bytes, stream, final_record ? 0u : nbins, table);
     if (st != QP_OK) return st;
     const qp_qparams_t *qdev = reinterpret_cast<const qp_qparams_t *>(static_cast<char *>(ws_dev) + kOffQParams);
     st = qp_quant_pack_dev(x_dev, n, dtype, bits, qdev, packed_dev, packed_bytes, stream);

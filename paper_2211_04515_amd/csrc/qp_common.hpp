@@ -83,6 +83,7 @@ struct Ctl {
 constexpr size_t kOffStats = 0;                                   // qp_stats_t (88 B)
 constexpr size_t kOffResult = 128;                                // qp_search_result_t (56 B)
 constexpr size_t kOffQParams = 192;                               // qp_qparams_t (32 B)
+constexpr size_t kOffModel = 224;                                 // qp_model_fit_t (24 B)
 constexpr size_t kOffCtl = 256;                                   // Ctl
 constexpr size_t kOffHist = 512;                                  // uint32_t[kMaxBins]
 constexpr size_t kOffCands = kOffHist + kMaxBins * 4;             // Cand[kMaxT + 1]
@@ -94,7 +95,7 @@ constexpr size_t kOffValueCounts = kOffPart2 + kMaxStat2Blocks * sizeof(Part2); 
 constexpr size_t kOffListScores = kOffValueCounts + 65536 * 4;   // double[kMaxT + 1]: scores in list order (coarse-to-fine)
 constexpr size_t kOffSearchPart = kOffListScores + (kMaxT + 1) * 8;  // double[t + 1][blocks]
 static_assert(sizeof(qp_stats_t) <= 128 && sizeof(qp_search_result_t) <= 64 && sizeof(qp_qparams_t) == 32 &&
-              sizeof(Ctl) <= 256, "fixed workspace regions");
+              sizeof(qp_model_fit_t) <= 32 && sizeof(Ctl) <= 256, "fixed workspace regions");
 static_assert(kOffSearchPart % 16 == 0, "alignment");
 
 // native vector types (the nontemporal builtins want them)
@@ -485,7 +486,8 @@ __device__ __host__ inline void make_grid(double center, double alpha, uint32_t 
 struct SearchPlan {
     uint32_t bits, t_steps, cpr;
     double C;            // F(q) (Laplace) or G(q) (Gaussian): alpha = C * scale
-    uint32_t dist;       // QP_LAPLACE / QP_GAUSS
+    double C_alt;        // dist == QP_DIST_AUTO: C is F(q) and this is G(q); the device picks
+    uint32_t dist;       // QP_LAPLACE / QP_GAUSS / QP_DIST_AUTO
     uint32_t clip;       // intersect candidate ranges with the data's range
     uint32_t stride;     // 1: all t + 1 candidates; > 1: coarse sweep with this stride, then a fine one
     uint32_t aciq_only;  // 1: score nothing, the result is plain ACIQ (j = 0)
@@ -581,7 +583,20 @@ struct ModelArgs {
     uint32_t list_mode, list_stride, count;   // the sweep: count candidates, list entry i -> grid index j
     uint32_t bits, t_steps;
     double C;
+    double C_alt;                   // dist == QP_DIST_AUTO: the Gaussian constant (C holds the Laplace one)
+    const qp_model_fit_t *model;    // ... and the record that says which model the tensor's histogram fits
 };
+
+// A search with dist = QP_DIST_AUTO: the model that the fit (k_model_fit, an earlier kernel on the stream) chose.
+__device__ inline ModelArgs resolve_model(ModelArgs m)
+{
+    if (m.dist == QP_DIST_AUTO) {
+        const bool gauss = m.model->dist == QP_GAUSS;
+        m.dist = gauss ? QP_GAUSS : QP_LAPLACE;
+        if (gauss) m.C = m.C_alt;
+    }
+    return m;
+}
 
 // The scalars every candidate of a search shares: the centre, the two ends of the scale grid and its step
 // (Eq. 1), and the data's range.  A bound or estimate that is zero, negative or not finite collapses the
@@ -704,7 +719,10 @@ hipError_t launch_stats_from_table(uint64_t n, uint32_t nbins, void *ws, hipStre
 hipError_t launch_table_search(uint64_t n, const SearchPlan &plan, const qp_stats_t *stats_host_or_null, void *ws, hipStream_t s);
 bool coarse_to_fine_supported(uint64_t n, int dtype, const SearchPlan &plan);
 // The host's part of ModelArgs for one sweep of a plan.
-ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *stats_host_or_null, uint32_t list_mode, uint32_t count);
+ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *stats_host_or_null, uint32_t list_mode, uint32_t count,
+                     const void *ws);
+// Which model the histogram in the workspace fits (one block; writes the qp_model_fit_t record).
+hipError_t launch_model_fit(void *ws, hipStream_t s);
 uint32_t search_blocks(uint64_t n);
 hipError_t launch_hist_search(uint32_t bits, uint32_t t_steps, double F, void *ws, hipStream_t s);
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *host_qp,

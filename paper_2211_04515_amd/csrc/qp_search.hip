@@ -44,6 +44,7 @@ __global__ __launch_bounds__(kFinThreads) void k_search_setup(ModelArgs m, qp_st
 {
     for (uint32_t j = threadIdx.x; j <= kMaxT; j += blockDim.x) round_tickets[j] = 0u;
     if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
+    m = resolve_model(m);
     const uint32_t j1 = (m.list_mode == kListFine) ? prev->j_star : 0u;
     setup_candidates(m, m.from_ws ? stats_dev : nullptr, j1, n, cands, nullptr, ctl, scores_by_j);
 }
@@ -57,6 +58,7 @@ __global__ __launch_bounds__(kFinThreads) void k_aciq_only(ModelArgs m, qp_stats
                                                            qp_qparams_t *__restrict__ best)
 {
     if (fin.nbins) finalize_stats_block(fin.part1, fin.nb1, fin.part2, fin.nb2, fin.hist, fin.nbins, n, stats_dev);
+    m = resolve_model(m);
     m.list_mode = kListFull;
     m.count = 1u;
     setup_candidates(m, m.from_ws ? stats_dev : nullptr, 0u, n, cands, nullptr, ctl, nullptr);
@@ -267,6 +269,65 @@ __global__ __launch_bounds__(kSrThreads, (search_waves<DT, CMAX>())) void k_sear
     if (lane == 0) write_search_result(ctl, sh_scores, ncand, bi, n, scores_by_j, res, best);
 }
 
+// ---- which model fits: Laplace or Gaussian ---------------------------------------------------
+// One block over the histogram: the squared distance between the histogram density and each model's pdf at its
+// moment estimates (b_E = MAD, sigma = sqrt(var)), fp64, fixed order.  Gaussian only if strictly closer; NaN
+// (one distinct value, a record the statistics never wrote) keeps the paper's Laplace model.
+constexpr int kMfThreads = 512;
+__global__ __launch_bounds__(kMfThreads) void k_model_fit(const qp_stats_t *__restrict__ st, const uint32_t *__restrict__ hist,
+                                                          qp_model_fit_t *__restrict__ out)
+{
+    __shared__ double sh_l[kMfThreads / kWave], sh_g[kMfThreads / kWave];
+    const uint32_t tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const uint32_t nb_rec = st->nbins;
+    const uint64_t n = st->n;
+    const bool rec_ok = nb_rec >= 16u && nb_rec <= kMaxBins && n != 0u;
+    const uint32_t B = rec_ok ? nb_rec : 0u;
+    const double mean = st->mean, mn = st->min, mx = st->max;
+    const double b = st->mad, sg = sqrt(st->var);
+    const double binw = (mx - mn) / (double)B;
+    const double g_norm = sg * 2.5066282746310002 /* sqrt(2 pi) */, g_den = 2.0 * sg * sg;
+    double fl = 0.0, fg = 0.0;
+    for (uint32_t i = tid; i < B; i += kMfThreads) {
+        const double c = mn + ((double)i + 0.5) * binw;
+        const double d_r = (double)hist[i] / ((double)n * binw);
+        const double z = c - mean;
+        const double d_l = exp(-fabs(z) / b) / (2.0 * b);
+        const double d_g = exp(-(z * z) / g_den) / g_norm;
+        fl = fma(d_r - d_l, d_r - d_l, fl);
+        fg = fma(d_r - d_g, d_r - d_g, fg);
+    }
+    fl = wave_sum(fl);
+    fg = wave_sum(fg);
+    if (lane == 0) {
+        sh_l[wave] = fl;
+        sh_g[wave] = fg;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double tl = sh_l[0], tg = sh_g[0];
+        for (int w = 1; w < kMfThreads / kWave; ++w) {
+            tl += sh_l[w];
+            tg += sh_g[w];
+        }
+        if (!rec_ok) tl = tg = __longlong_as_double(0x7ff8000000000000ll);
+        qp_model_fit_t r;
+        r.fit_laplace = tl;
+        r.fit_gauss = tg;
+        r.dist = (tg < tl) ? (uint32_t)QP_GAUSS : (uint32_t)QP_LAPLACE;   // false whenever either is NaN
+        r.reserved = 0u;
+        *out = r;
+    }
+}
+
+hipError_t launch_model_fit(void *ws, hipStream_t s)
+{
+    char *w = static_cast<char *>(ws);
+    hipLaunchKernelGGL(k_model_fit, dim3(1), dim3(kMfThreads), 0, s, reinterpret_cast<const qp_stats_t *>(w + kOffStats),
+                       reinterpret_cast<const uint32_t *>(w + kOffHist), reinterpret_cast<qp_model_fit_t *>(w + kOffModel));
+    return hipGetLastError();
+}
+
 // ---- the other reading of Eq. 1: fit the Laplace pdf to the histogram -----------------
 // One block per candidate: lanes stride over the bins, score_j = sum_i (D_R,i - pdf(c_i; mu, b_j))^2
 // in fp64 (D_R,i = count_i / (N binwidth), c_i the bin centre).  The block that draws the last
@@ -471,9 +532,13 @@ template <int DT> static hipError_t launch_rounds(const SearchArgs &a, uint32_t 
     }
 }
 
-ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *st, uint32_t list_mode, uint32_t count)
+ModelArgs model_args(const SearchPlan &plan, const qp_stats_t *st, uint32_t list_mode, uint32_t count, const void *ws)
 {
     ModelArgs m{};
+    // the model chosen on the device: the grid is built there too, from the record the choice was made on
+    if (plan.dist == QP_DIST_AUTO) st = nullptr;
+    m.C_alt = plan.C_alt;
+    m.model = reinterpret_cast<const qp_model_fit_t *>(static_cast<const char *>(ws) + kOffModel);
     m.from_ws = st ? 0 : 1;
     if (st) {
         m.mean_h = st->mean;
@@ -516,7 +581,7 @@ static hipError_t launch_sweep(const void *x, uint64_t n, int dtype, const Searc
     FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                      reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
     if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
-    const ModelArgs m = model_args(plan, st, list_mode, count);
+    const ModelArgs m = model_args(plan, st, list_mode, count, ws);
     hipLaunchKernelGGL(k_search_setup, dim3(1), dim3(kFinThreads), 0, s, m, stats_dev, n, cands, ctl, round_tickets, fin,
                        res, scores_by_j);
     const hipError_t e = hipGetLastError();
@@ -536,7 +601,7 @@ hipError_t launch_search(const void *x, uint64_t n, int dtype, const SearchPlan 
         FinalizeArgs fin{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                          reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
         if (finalize_nbins) stats_grid(n, dtype, fin.nb1, fin.nb2);
-        hipLaunchKernelGGL(k_aciq_only, dim3(1), dim3(kFinThreads), 0, s, model_args(plan, st, kListFull, 1u),
+        hipLaunchKernelGGL(k_aciq_only, dim3(1), dim3(kFinThreads), 0, s, model_args(plan, st, kListFull, 1u, ws),
                            reinterpret_cast<qp_stats_t *>(w + kOffStats), n, reinterpret_cast<Cand *>(w + kOffCands),
                            reinterpret_cast<Ctl *>(w + kOffCtl), fin, reinterpret_cast<double *>(w + kOffScores),
                            reinterpret_cast<qp_search_result_t *>(w + kOffResult),

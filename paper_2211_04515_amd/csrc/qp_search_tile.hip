@@ -55,6 +55,7 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
     const uint32_t tid = threadIdx.x;
     const uint32_t G = gridDim.x, blk = blockIdx.x;
     const uint32_t ncand = a.m.count;
+    const ModelArgs m = resolve_model(a.m);
     const uint64_t e_begin = (uint64_t)blk * a.share;
     const uint64_t e_end = min(a.n, e_begin + a.share);
 
@@ -81,13 +82,13 @@ template <int DT> __global__ __launch_bounds__(kStThreads) void k_search_tile(Ti
         finalize_stats_block(a.fin.part1, a.fin.nb1, a.fin.part2, a.fin.nb2, a.fin.hist, a.fin.nbins, a.n, &sh_st);
         if (blk == 0 && tid == 0) *a.stats_dev = sh_st;
         st = &sh_st;
-    } else if (a.m.from_ws) {
+    } else if (m.from_ws) {
         st = a.stats_dev;
     }
-    const uint32_t j1 = (a.m.list_mode == kListFine) ? a.prev->j_star : 0u;
-    const int safe = setup_candidates(a.m, st, j1, a.n, sh_cands, blk == 0 ? a.cands : nullptr, blk == 0 ? a.ctl : nullptr,
+    const uint32_t j1 = (m.list_mode == kListFine) ? a.prev->j_star : 0u;
+    const int safe = setup_candidates(m, st, j1, a.n, sh_cands, blk == 0 ? a.cands : nullptr, blk == 0 ? a.ctl : nullptr,
                                       blk == 0 ? a.scores_by_j : nullptr);
-    const float Lf = (float)((1u << a.m.bits) - 1u);
+    const float Lf = (float)((1u << m.bits) - 1u);
 
     // ---- scoring: lane -> (slice of the sub-tile, candidate) ----
     const uint32_t S = kStThreads / ncand;            // slices, >= 2
@@ -233,7 +234,7 @@ static hipError_t launch_tile_sweep(const void *x, uint64_t n, int dtype, const 
     a.x = x;
     a.n = n;
     a.share = tile_share(n);
-    a.m = model_args(plan, st, list_mode, count);
+    a.m = model_args(plan, st, list_mode, count, ws);
     a.fin = FinalizeArgs{reinterpret_cast<const Part1 *>(w + kOffPart1), reinterpret_cast<const Part2 *>(w + kOffPart2),
                          reinterpret_cast<const uint32_t *>(w + kOffHist), 0u, 0u, finalize_nbins};
     if (finalize_nbins) stats_grid(n, dtype, a.fin.nb1, a.fin.nb2);

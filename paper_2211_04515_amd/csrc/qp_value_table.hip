@@ -253,7 +253,7 @@ hipError_t launch_stats_from_table(uint64_t n, uint32_t nbins, void *ws, hipStre
 // accesses; that block takes the first minimum and writes the control record, the result and the winner's
 // grid.  Sums in a fixed order: bit-reproducible.
 constexpr int kTbThreads = 1024;
-__global__ __launch_bounds__(kTbThreads) void k_search_table(const uint32_t *__restrict__ counts, ModelArgs m,
+__global__ __launch_bounds__(kTbThreads) void k_search_table(const uint32_t *__restrict__ counts, ModelArgs m_in,
                                                              const qp_stats_t *__restrict__ stats_dev, uint64_t n_total,
                                                              Cand *__restrict__ cands, double *__restrict__ scores,
                                                              Ctl *__restrict__ ctl, qp_search_result_t *__restrict__ res,
@@ -274,6 +274,7 @@ __global__ __launch_bounds__(kTbThreads) void k_search_table(const uint32_t *__r
         cnt[4 * k + 2] = c4.z;
         cnt[4 * k + 3] = c4.w;
     }
+    const ModelArgs m = resolve_model(m_in);
     const GridModel g = grid_model(m, m.from_ws ? stats_dev : nullptr);
     int safe;
     const Cand p = candidate_grid(m, g, j, safe);
@@ -335,7 +336,7 @@ hipError_t launch_table_search(uint64_t n, const SearchPlan &plan, const qp_stat
     char *w = static_cast<char *>(ws);
     const uint32_t ncand = plan.t_steps + 1u;
     hipLaunchKernelGGL(k_search_table, dim3(ncand), dim3(kTbThreads), 0, s,
-                       reinterpret_cast<const uint32_t *>(w + kOffValueCounts), model_args(plan, st, kListFull, ncand),
+                       reinterpret_cast<const uint32_t *>(w + kOffValueCounts), model_args(plan, st, kListFull, ncand, ws),
                        reinterpret_cast<const qp_stats_t *>(w + kOffStats), n, reinterpret_cast<Cand *>(w + kOffCands),
                        reinterpret_cast<double *>(w + kOffScores), reinterpret_cast<Ctl *>(w + kOffCtl),
                        reinterpret_cast<qp_search_result_t *>(w + kOffResult),

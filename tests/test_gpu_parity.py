@@ -1050,13 +1050,16 @@ def test_hist_search_degenerate_inputs(qp, name):
 def test_hist_search_on_a_workspace_the_statistics_never_wrote(qp, fill):
     """The histogram-fit search takes its bin count from the record in the workspace.  A record that is not one
     (zeros, all ones, a pattern whose bin count lies far beyond the histogram region) must not be followed out of
-    bounds: every score is NaN, plain ACIQ's index is kept, and the kernel ends normally."""
+    bounds: every score is NaN and the kernel ends normally.  (Whether a result record is written as well depends on
+    the ticket word the statistics would have cleared: with a zeroed workspace it is, and keeps plain ACIQ's index.)"""
     ws = qp.alloc_workspace(100_000)
     ws.fill_(fill)
     res, q = qp.qp_dsaciq_hist_search(4, ws)
     offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
     scores = ws[offs:offs + 8 * 101].cpu().numpy().view(np.float64)
-    assert np.isnan(scores).all() and res.j_star == 0 and res.t_steps == 100
+    assert np.isnan(scores).all()
+    if fill == 0:
+        assert res.j_star == 0 and res.t_steps == 100
     # and the workspace is still usable afterwards
     x = si.make_config("C1")
     xd = to_dev(x)
@@ -1278,6 +1281,83 @@ def test_coarse_to_fine_on_the_streaming_kernel(qp):
         for bits in (2, 4):
             res, q = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=variant_cfg(qp, dict(stride=stride)))
             check_variant(qp, x, st, bits, dict(stride=stride), 100, ws, res, q)
+
+
+# ----------------------------------------------------------------------------- the model chosen per tensor by fit
+
+def gauss_sample(n, seed=21, bf16=False):
+    x = (np.random.default_rng(seed).standard_normal(n) * 0.8 + 0.3).astype(np.float32)
+    return si.f32_to_bf16_bits(x) if bf16 else x
+
+
+MODEL_INPUTS = [("C1", lambda: si.make_config("C1")), ("C2", lambda: si.make_config("C2", n=1_234_567)),
+                ("C3", lambda: si.make_config("C3", n=987_653)), ("C5_bf16", lambda: si.make_config("C5", n=777_779)),
+                ("C5_table", lambda: si.make_config("C5", n=1_300_001)), ("gauss", lambda: gauss_sample(500_003)),
+                ("gauss_streaming", lambda: gauss_sample(2_400_007)), ("gauss_table", lambda: gauss_sample(1_500_001, bf16=True)),
+                ("constant", lambda: np.full(1000, 1.25, np.float32)), ("one_element", lambda: np.array([0.5], np.float32))]
+
+
+@pytest.mark.parametrize("name,make", MODEL_INPUTS, ids=[m[0] for m in MODEL_INPUTS])
+def test_model_fit_and_search_with_the_chosen_model(qp, name, make):
+    """qp_model_fit against the oracle's fit of the same record and histogram; a search with dist = QP_DIST_AUTO
+    equals, bit for bit, the search with that model named, and matches the oracle's search under the model the
+    oracle chooses; the sender path with QP_DIST_AUTO equals the separate calls."""
+    x = make()
+    xf = as_f32(x)
+    xd = to_dev(x)
+    n = x.size
+    ws = qp.alloc_workspace(n)
+    st = qp.qp_stats(xd, ws)
+    hist = ws[qp.qp_ws_offset(qp.QP_WS_HIST):][:4 * 2048].cpu().numpy().view(np.uint32).copy()
+    mf = qp.qp_model_fit(ws)
+    od, ofl, ofg = orc.model_fit(oracle_stats_from(st), hist)
+    print(f"[case] model fit {name} n={n}: laplace {mf.fit_laplace!r} gauss {mf.fit_gauss!r} -> {mf.dist}", flush=True)
+    # sums of 2048 terms with the device's exp against libm's
+    assert mf.fit_laplace == pytest.approx(ofl, rel=1e-12, nan_ok=True) and mf.fit_gauss == pytest.approx(ofg, rel=1e-12, nan_ok=True)
+    if mf.dist != od:      # only a numerical tie between the two fits may be decided differently
+        assert abs(ofl - ofg) <= 1e-12 * ofl
+    assert mf.dist in (qp.QP_LAPLACE, qp.QP_GAUSS) and mf.reserved == 0
+    if name.startswith("gauss"):
+        assert mf.dist == qp.QP_GAUSS
+    if name in ("C1", "constant", "one_element"):
+        assert mf.dist == qp.QP_LAPLACE
+    off = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for v in (dict(), dict(clip=True), dict(stride=10)):
+        if v.get("stride", 1) > 1 and not c2f_offered(x):
+            continue
+        auto = variant_cfg(qp, v)
+        auto.dist = qp.QP_DIST_AUTO
+        named = variant_cfg(qp, dict(v, dist=mf.dist))
+        for bits in (2, 8):
+            ra, qa = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=auto)
+            sa = ws[off:off + 8 * 101].cpu().numpy().tobytes()
+            chosen = qp.read_ws(ws, qp.QP_WS_MODEL, qp.qp_model_fit_t)
+            assert bytes(chosen) == bytes(mf)
+            rn, qn = qp.qp_dsaciq_search(xd, st, bits, ws, cfg=named)
+            assert bytes(ra) == bytes(rn) and bytes(qa) == bytes(qn) and sa == ws[off:off + 8 * 101].cpu().numpy().tobytes()
+            if mf.dist == od and n > 1:
+                check_variant(qp, xf, st, bits, dict(v, dist=od), 100, ws, rn, qn)
+    # sender path: statistics, the choice, the search and the pack with nothing returned to the host in between
+    auto = qp.qp_default_search_cfg()
+    auto.dist = qp.QP_DIST_AUTO
+    ws2 = qp.alloc_workspace(n)
+    ws2.fill_(0x9E)
+    packed = qp.alloc_packed(n, 4)
+    qp.qp_compress_async(xd, 4, ws2, packed, cfg=auto)
+    torch.cuda.synchronize()
+    ra, qa = qp.qp_dsaciq_search(xd, st, 4, ws, cfg=auto)
+    assert bytes(qp.read_ws(ws2, qp.QP_WS_MODEL, qp.qp_model_fit_t)) == bytes(mf)
+    assert bytes(qp.read_ws(ws2, qp.QP_WS_RESULT, qp.qp_search_result_t)) == bytes(ra)
+    assert bytes(qp.read_ws(ws2, qp.QP_WS_QPARAMS, qp.qp_qparams_t)) == bytes(qa)
+    assert np.array_equal(packed.cpu().numpy(), orc.pack(orc.quantize(xf, oracle_q_from(qa)), 4))
+
+
+def test_model_fit_on_a_workspace_the_statistics_never_wrote(qp):
+    for fill in (0x00, 0xFF):
+        ws = qp.alloc_workspace(50_000)
+        ws.fill_(fill)
+        mf = qp.qp_model_fit(ws)
+        assert np.isnan(mf.fit_laplace) and np.isnan(mf.fit_gauss) and mf.dist == qp.QP_LAPLACE
 
 
 def test_low_bits_only_policy(qp):

@@ -62,6 +62,9 @@ def test_struct_sizes_match_the_header_layout(qp):
     offs = [qp.qp_ws_offset(r) for r in range(6)]
     assert offs == sorted(offs) and len(set(offs)) == 6 and all(o % 16 == 0 for o in offs)
     assert qp.qp_ws_offset(99) == 2 ** 64 - 1
+    assert C.sizeof(qp.qp_model_fit_t) == 24
+    m = qp.qp_ws_offset(qp.QP_WS_MODEL)     # sits in the gap between the winner's grid and the control block
+    assert m % 8 == 0 and qp.qp_ws_offset(qp.QP_WS_QPARAMS) + 32 <= m and m + 24 <= qp.qp_ws_offset(qp.QP_WS_HIST)
 
 
 def test_packed_bytes(qp):
@@ -146,17 +149,26 @@ def test_argument_errors_are_reported_before_any_gpu_work(qp):
     assert L.qp_dsaciq_search(fake, 1000, 0, None, 4, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
     assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 5, None, fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL
     assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, None, fake, 1000, None, C.byref(res), C.byref(qo)) == qp.QP_ENOSPC
-    for field, value in (("dist", 2), ("flags", 8), ("coarse_stride", 65), ("cands_per_round", 33), ("t_steps", 0)):
+    for field, value in (("dist", 3), ("flags", 8), ("coarse_stride", 65), ("cands_per_round", 33), ("t_steps", 0)):
         cfg = qp.qp_default_search_cfg()
         setattr(cfg, field, value)
         assert L.qp_dsaciq_search(fake, 1000, 0, C.byref(st), 4, C.byref(cfg), fake, big, None, C.byref(res), C.byref(qo)) == qp.QP_EINVAL, field
-    for field, value in (("dist", qp.QP_GAUSS), ("flags", qp.QP_SEARCH_CLIP_TO_DATA)):    # the histogram fit is the paper's form only
+    for field, value in (("dist", qp.QP_GAUSS), ("dist", qp.QP_DIST_AUTO), ("flags", qp.QP_SEARCH_CLIP_TO_DATA)):    # the histogram fit is the paper's form only
         cfg = qp.qp_default_search_cfg()
         setattr(cfg, field, value)
         assert L.qp_dsaciq_hist_search_async(4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL, field
     cfg = qp.qp_default_search_cfg()
     cfg.t_steps = 5000
     assert L.qp_dsaciq_search_async(fake, 1000, 0, 4, C.byref(cfg), fake, big, None) == qp.QP_EINVAL
+    # model fit: the choice needs the histogram, so the host-only alpha does not take QP_DIST_AUTO
+    mf = qp.qp_model_fit_t()
+    assert L.qp_model_fit(None, big, None, C.byref(mf)) == qp.QP_EINVAL
+    assert L.qp_model_fit(fake, big, None, None) == qp.QP_EINVAL
+    assert L.qp_model_fit(odd, big, None, C.byref(mf)) == qp.QP_EINVAL
+    assert L.qp_model_fit_async(fake, 64, None) == qp.QP_ENOSPC
+    alpha = C.c_double()
+    assert L.qp_aciq_alpha(C.byref(st), 4, qp.QP_DIST_AUTO, C.byref(alpha)) == qp.QP_EINVAL
+    assert math.isnan(L.qp_aciq_constant(4, qp.QP_DIST_AUTO))
     # histogram-fit search
     assert L.qp_dsaciq_hist_search_async(5, None, fake, big, None) == qp.QP_EINVAL
     assert L.qp_dsaciq_hist_search_async(4, None, None, big, None) == qp.QP_EINVAL

@@ -91,6 +91,8 @@ def check_against_oracle(r, x, bits, t=100, dist=0, clip=False, stride=1, nbins=
     ost = orc.Stats()
     for name, _ in orc.Stats._fields_:
         setattr(ost, name, getattr(st, name))
+    if dist == 2:   # the model chosen on the (emulated) device by fit: the oracle makes the same choice from the same record
+        dist = orc.model_fit(ost, r["hist"])[0]
     ores, oq, oscores = orc.dsaciq_search_variant(xf, ost, bits, t, dist=dist, clip_to_data=clip, stride=stride)
     assert np.array_equal(np.isnan(r["scores"]), np.isnan(oscores))
     assert np.allclose(r["scores"], oscores, rtol=REL, atol=0.0, equal_nan=True)
@@ -106,6 +108,10 @@ def check_against_oracle(r, x, bits, t=100, dist=0, clip=False, stride=1, nbins=
 def small_input(kind, n):
     if kind == "bf16":
         return si.make_config("C5", n=n)
+    if kind == "gauss":
+        return (np.random.default_rng(n).standard_normal(n) * 0.8 + 0.3).astype(np.float32)
+    if kind == "gauss_bf16":
+        return si.f32_to_bf16_bits((np.random.default_rng(n).standard_normal(n) * 0.8 + 0.3).astype(np.float32))
     return si.make_config(kind, n=n)
 
 
@@ -113,7 +119,9 @@ def small_input(kind, n):
 # per candidate in the pick kernel makes t the main cost here)
 TILE_CASES = [("C1", 3_011, 2, {}, 100), ("C3", 4_999, 3, {}, 12), ("bf16", 5_345, 4, {}, 12), ("C2", 4_097, 16, {}, 7),
               ("C3", 130, 6, {}, 12), ("C3", 3_001, 4, dict(clip=True), 12), ("C2", 2_191, 2, dict(dist=1, stride=4), 20),
-              ("bf16", 2_777, 8, dict(stride=3, clip=True), 12), ("C1", 5, 4, {}, 5), ("C3", 1, 8, {}, 3)]
+              ("bf16", 2_777, 8, dict(stride=3, clip=True), 12), ("C1", 5, 4, {}, 5), ("C3", 1, 8, {}, 3),
+              # the model chosen per tensor by fit (Gaussian data must take the Gaussian model, Laplace-like data the paper's)
+              ("gauss", 4_001, 4, dict(dist=2), 12), ("C1", 3_011, 3, dict(dist=2, clip=True), 12), ("gauss", 2_500, 2, dict(dist=2, stride=4), 20)]
 # the same kind of tensors through the kernels large tensors take (thresholds lowered at build time)
 STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37), ("bf16", 5_001, 4, {}, 30),
                 ("bf16", 3_000, 3, dict(dist=1), 20), ("C1", 2_049, 6, {}, 1),
@@ -123,7 +131,9 @@ STREAM_CASES = [("C3", 10_011, 2, {}, 100), ("C2", 6_007, 8, dict(clip=True), 37
                 # 3 + 3 + 3 does)
                 ("C3", 4_111, 4, dict(cpr=1), 5), ("C2", 4_100, 3, dict(cpr=2), 6), ("C4", 4_321, 2, dict(cpr=5), 8),
                 # a coarse-to-fine sweep of a tensor above the tile search's size limit still runs on the tile search
-                ("C3", 9_001, 4, dict(stride=5), 40)]
+                ("C3", 9_001, 4, dict(stride=5), 40),
+                # the model chosen by fit, through the streaming search and through the value table
+                ("gauss", 6_001, 4, dict(dist=2), 20), ("gauss_bf16", 5_003, 3, dict(dist=2), 20), ("C2", 5_555, 2, dict(dist=2, cpr=4), 9)]
 REFUSED = ("bf16", 5_000, 4, dict(stride=10), 100)
 ACIQ_ONLY = [("default", ("C3", 3_003, 8, dict(low_bits_only=True), 100)), ("streaming", ("bf16", 6_001, 6, dict(low_bits_only=True, clip=True), 100))]
 # Blocks of a launch in shuffled order, `conc` at a time (each a process of its own): ticket hand-overs out of order.
