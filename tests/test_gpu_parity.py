@@ -1114,6 +1114,42 @@ def test_bf16_value_table_search_edge_cases(qp, kind):
         assert res.mse_star == pytest.approx(scores[res.j_star] / n, rel=1e-15) or np.isnan(res.mse_star)
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("kind", ["constant", "three_values", "hot_value_in_noise"])
+def test_bf16_value_table_counters_with_hot_values(qp, kind):
+    """Large bf16 tensors whose elements pile onto one or a few values (every lane's increment of the value table
+    then hits the same counter, and two of the values differ in sign only): the table's statistics, histogram and
+    scores must still be the oracle's."""
+    n = (1 << 25) + 13                       # 33.5 M elements
+    rng = np.random.default_rng(41)
+    if kind == "constant":
+        h = si.f32_to_bf16_bits(np.full(n, -0.75, np.float32))
+    elif kind == "three_values":             # two of them have the same magnitude and opposite signs
+        h = si.f32_to_bf16_bits(np.array([1.5, -1.5, 0.25], np.float32))[rng.integers(0, 3, size=n)]
+    else:                                    # 60 % of the elements are one value, the rest Laplace noise
+        x = rng.laplace(0.1, 0.5, size=n).astype(np.float32)
+        x[rng.random(n) < 0.6] = 0.625
+        h = si.f32_to_bf16_bits(x)
+    xf = orc.widen_bf16(h)
+    xd = to_dev(h)
+    ws = qp.alloc_workspace(n)
+    st = qp.qp_stats(xd, ws)
+    rc, ost, hist_ref = orc.stats(xf, want_hist=True)
+    assert (st.n, st.min, st.max, st.peak_count) == (n, ost.min, ost.max, ost.peak_count)
+    for f in ("mean", "mad", "abs_mean", "var"):
+        assert abs(getattr(st, f) - getattr(ost, f)) <= REL_STATS_FULL * max(abs(getattr(ost, f)), 1e-3 * ost.abs_mean), f
+    off = qp.qp_ws_offset(qp.QP_WS_HIST)
+    assert np.array_equal(ws[off:off + 8192].cpu().numpy().view(np.uint32), hist_ref[:2048])
+    offs = qp.qp_ws_offset(qp.QP_WS_SCORES)
+    for bits in (2, 4):
+        res, q = qp.qp_dsaciq_search(xd, st, bits, ws)
+        scores = ws[offs:offs + 8 * 101].cpu().numpy().view(np.float64)
+        ores, oq, oscores = orc.dsaciq_search_threads(xf, oracle_stats_from(st), bits, 100, ORACLE_THREADS)
+        assert np.allclose(scores, oscores, rtol=rel_score_sequential(n), atol=0.0, equal_nan=True)
+        if check_winner(xf, oracle_stats_from(st), bits, res.j_star, ores):
+            assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+
+
 # ----------------------------------------------------------------------------- variants of the search
 # (Gaussian model, ranges intersected with the data's, coarse-to-fine sweep) against their own oracle
 
