@@ -256,7 +256,7 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
             qp.qp_unpack_dequant_dev(packs[b][r % NBUF], b, qdev, ys[r % NBUF])
     tpol = timed_reps(policy_step)
 
-    # Where the floor of a launch of this size is: the same two kernels at 4 bit on 1, 2, 4 and 8 copies of the tensor
+    # Where the floor of a launch of this size is: pack and unpack at 4 bit, and the statistics, on 1, 2, 4 and 8 copies of the tensor
     # laid end to end (38.7 to 310 MB in), each size over enough rotating buffers to exceed the Infinity Cache;
     # least-squares fit of us = fixed + bytes / rate.  The fixed part (launch, ramp to full bandwidth, drain) is what
     # keeps a 40 MB launch below the rate the same kernel reaches on a large tensor.
@@ -298,7 +298,7 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
 def size_sweep(qp, torch, x_host, timed_reps):
     import numpy as np
     n1 = x_host.size
-    rows, pts_p, pts_u = [], [], []
+    rows, pts_p, pts_u, pts_s = [], [], [], []
     for m in (1, 2, 4, 8):
         n = n1 * m
         nb = max(3, 16 // m)
@@ -308,12 +308,16 @@ def size_sweep(qp, torch, x_host, timed_reps):
         q = qp.qp_make_qparams(0.0, 2.5, 4, n)
         tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, pk[r % nb]))
         tu = timed_reps(lambda r: qp.qp_unpack_dequant(pk[r % nb], q, ys[r % nb]))
+        ws = qp.alloc_workspace(n)
+        ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
         byts = n * 4 + n * 4 / 8
         rows.append({"elements": n, "bytes": byts, "pack_us": tp, "pack_frac_hbm": byts / tp / 1e3 / HBM_PEAK_GBS,
-                     "unpack_us": tu, "unpack_frac_hbm": byts / tu / 1e3 / HBM_PEAK_GBS})
+                     "unpack_us": tu, "unpack_frac_hbm": byts / tu / 1e3 / HBM_PEAK_GBS,
+                     "stats_bytes": 2 * n * 4, "stats_us": ts, "stats_frac_hbm": 2 * n * 4 / ts / 1e3 / HBM_PEAK_GBS})
         pts_p.append((byts, tp))
         pts_u.append((byts, tu))
-        del xs, ys, pk
+        pts_s.append((2 * n * 4, ts))
+        del xs, ys, pk, ws
 
     def fit(pts):
         a = np.array([[1.0, b] for b, _ in pts])
@@ -321,7 +325,7 @@ def size_sweep(qp, torch, x_host, timed_reps):
         (fixed, slope), *_ = np.linalg.lstsq(a, t, rcond=None)
         return {"fixed_us": float(fixed), "asymptotic_GBs": float(1.0 / slope / 1e3),
                 "asymptotic_frac_hbm": float(1.0 / slope / 1e3 / HBM_PEAK_GBS)}
-    return {"sizes": rows, "fit_pack": fit(pts_p), "fit_unpack": fit(pts_u)}
+    return {"sizes": rows, "fit_pack": fit(pts_p), "fit_unpack": fit(pts_u), "fit_stats_two_launches": fit(pts_s)}
 
 
 def c3_leg(qp, si, torch, timed_reps, reps):
