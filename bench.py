@@ -53,9 +53,9 @@ ALL_LEGS = ("c2", "c3", "c5", "c1", "c4", "cpu")
 # not measured by this process: a changed kernel shows in them only when those summaries are regenerated.
 TRAFFIC_RATIO = {
     # profiles/hbm_traffic_C2_fp32.txt
-    "c2_search_bytes": 89.74e6, "c2_pack": 1.0003, "c2_unpack": 1.003, "c2_stats": 1.0065,
+    "c2_search_bytes": 118.76e6, "c2_pack": 1.0002, "c2_unpack": 1.0032, "c2_stats": 1.0063,
     # profiles/hbm_traffic_C5_bf16.txt
-    "c5_value_hist": 1.0, "c5_pack": 1.0, "c5_unpack": 1.0,
+    "c5_value_hist": 1.0094, "c5_pack": 1.0001, "c5_unpack": 1.0024,
 }
 TRAFFIC_SOURCE = {"c2": "profiles/hbm_traffic_C2_fp32.txt", "c5": "profiles/hbm_traffic_C5_bf16.txt"}
 
@@ -86,6 +86,9 @@ def main() -> int:
                          "c2 leg; without it only the chosen legs run and `value` is null (for profiles of one leg)")
     ap.add_argument("--kernel-reps", type=int, default=64, help="back-to-back launches per kernel timing")
     ap.add_argument("--c4-microbatches", type=int, default=500)
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="leave the size sweep out of the c2 leg (it launches the same kernels on larger tensors, which would "
+                         "mix into a profiler's per-kernel averages)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (tensors shard by microbatch with no exchange); "
@@ -260,7 +263,7 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
     # laid end to end (38.7 to 310 MB in), each size over enough rotating buffers to exceed the Infinity Cache;
     # least-squares fit of us = fixed + bytes / rate.  The fixed part (launch, ramp to full bandwidth, drain) is what
     # keeps a 40 MB launch below the rate the same kernel reaches on a large tensor.
-    sweep = size_sweep(qp, torch, x_host, timed_reps)
+    sweep = None if args.no_sweep else size_sweep(qp, torch, x_host, timed_reps)
 
     # headline for pack / unpack: the mean over the six bitwidths of the workload
     pack_bytes = sum(in_bytes + n * b / 8 for b in bits_set)
