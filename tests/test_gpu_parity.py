@@ -11,6 +11,13 @@ from oracle import qp_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
+
+def print(*args, **kwargs):
+    """The tests' "[case] ..." lines go to the real stderr, unbuffered: a run that faults or hangs has named its case."""
+    import builtins
+    import sys
+    builtins.print(*args, **{**kwargs, "file": sys.__stderr__, "flush": True})
+
 torch = pytest.importorskip("torch")
 BITS = (2, 3, 4, 6, 8, 16)
 
