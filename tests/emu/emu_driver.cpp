@@ -89,6 +89,9 @@ int main(int argc, char **argv)
     dump(out, "result.bin", &res, sizeof res);
     dump(out, "qparams.bin", &q, sizeof q);
     dump(out, "scores.bin", (const char *)ws + qp_ws_offset(QP_WS_SCORES), ((size_t)cfg.t_steps + 1) * 8);
+    // what the fused sender path left in its own workspace (its search may run a different kernel sequence)
+    dump(out, "scores2.bin", (const char *)ws2 + qp_ws_offset(QP_WS_SCORES), ((size_t)cfg.t_steps + 1) * 8);
+    dump(out, "result2.bin", (const char *)ws2 + qp_ws_offset(QP_WS_RESULT), sizeof res);
     dump(out, "packed.bin", packed, pkb);
     dump(out, "y.bin", y, n * 4);
     char line[256];

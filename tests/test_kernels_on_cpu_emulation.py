@@ -74,6 +74,7 @@ def read_outputs(p, out_dir):
                 res=Result.from_buffer_copy(open(path("result.bin"), "rb").read()),
                 q=QParams.from_buffer_copy(open(path("qparams.bin"), "rb").read()),
                 hist=rd("hist.bin", np.uint32), scores=rd("scores.bin", np.float64), packed=rd("packed.bin", np.uint8),
+                scores2=rd("scores2.bin", np.float64), res2=Result.from_buffer_copy(open(path("result2.bin"), "rb").read()),
                 y=rd("y.bin", np.float32))
 
 
@@ -96,6 +97,11 @@ def check_against_oracle(r, x, bits, t=100, dist=0, clip=False, stride=1, nbins=
     ores, oq, oscores = orc.dsaciq_search_variant(xf, ost, bits, t, dist=dist, clip_to_data=clip, stride=stride)
     assert np.array_equal(np.isnan(r["scores"]), np.isnan(oscores))
     assert np.allclose(r["scores"], oscores, rtol=REL, atol=0.0, equal_nan=True)
+    # the fused sender path's own search (for small tensors: the pick folded into the search kernel)
+    assert np.array_equal(np.isnan(r["scores2"]), np.isnan(oscores))
+    assert np.allclose(r["scores2"], oscores, rtol=REL, atol=0.0, equal_nan=True)
+    assert (r["res2"].j_star, r["res2"].t_steps) == (ores.j_star, t)
+    assert r["res2"].mse_star == pytest.approx(ores.mse_star, rel=REL, nan_ok=True) and r["res2"].mse_aciq == pytest.approx(ores.mse_aciq, rel=REL, nan_ok=True)
     res, q = r["res"], r["q"]
     assert res.j_star == ores.j_star and res.t_steps == t
     assert res.alpha_star == pytest.approx(ores.alpha_star, rel=1e-14)
