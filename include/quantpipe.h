@@ -294,8 +294,8 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
  * callers that cannot bring a workspace.  Same kernels and same results as qp_compress_async, with
  * the workspace in a static device array inside the library (1,384,960 bytes per GPU, held until
- * the process ends; its device address is looked up on the first call on each device).  Calls
- * no allocating routine.  The caller still owns x_dev, packed_dev and qparams_out_dev (required:
+ * the process ends; its device address is looked up on the first call on each device, so a caller
+ * that captures into a HIP graph makes one call outside the capture first).  Calls no allocating routine.  The caller still owns x_dev, packed_dev and qparams_out_dev (required:
  * 32 bytes of device memory that receive the winner's qp_qparams_t; the statistics and the search
  * result stay inside the library).  Limits: cfg->t_steps <= 127 (QP_ENOSPC beyond; NULL cfg =
  * the paper's 100), any n the other calls take.  Every call on a GPU uses that GPU's one array:

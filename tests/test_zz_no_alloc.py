@@ -104,3 +104,38 @@ def test_no_alloc_entry_point_rejects_what_it_cannot_hold(qp):
     assert L.qp_compress_noalloc(vp(xd.data_ptr()), x.size, 0, 5, None, vp(packed.data_ptr()), packed.numel(), vp(rec.data_ptr()), None) == qp.QP_EINVAL
     assert L.qp_compress_noalloc(vp(xd.data_ptr()), x.size, 0, 4, None, vp(packed.data_ptr()), 8, vp(rec.data_ptr()), None) == qp.QP_ENOSPC
     assert L.qp_compress_noalloc(vp(xd.data_ptr()), 0, 0, 4, None, vp(packed.data_ptr()), packed.numel(), vp(rec.data_ptr()), None) == qp.QP_EINVAL
+
+
+def test_no_alloc_entry_point_replays_from_a_hip_graph(qp):
+    """Callers under graph capture are whom the entry point is for: after one call outside the capture (the array's
+    address is looked up then) it captures, and every replay reproduces the eager result, with the program's own
+    eager work between the replays."""
+    n = 600_011
+    x1, x2 = si.make_config("C2", n=n), si.make_config("C3", n=n)
+    xin = to_dev(x1).clone()
+    packed = qp.alloc_packed(n, 3)
+    rec = torch.zeros(32, dtype=torch.uint8, device="cuda")
+
+    def eager(src):
+        xin.copy_(to_dev(src))
+        qp.qp_compress_noalloc(xin, 3, packed, rec.data_ptr())
+        torch.cuda.synchronize()
+        return packed.clone(), rec.clone()
+
+    ref1, ref2 = eager(x1), eager(x2)
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        qp.qp_compress_noalloc(xin, 3, packed, rec.data_ptr())
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        qp.qp_compress_noalloc(xin, 3, packed, rec.data_ptr())
+    torch.cuda.synchronize()
+    for rep, (src, ref) in enumerate(((x1, ref1), (x2, ref2), (x1, ref1))):
+        xin.copy_(to_dev(src))
+        packed.zero_()
+        rec.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(packed, ref[0]) and torch.equal(rec, ref[1]), rep
