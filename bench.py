@@ -60,6 +60,27 @@ TRAFFIC_RATIO = {
 TRAFFIC_SOURCE = {"c2": "profiles/hbm_traffic_C2_fp32.txt", "c5": "profiles/hbm_traffic_C5_bf16.txt"}
 
 
+COLD_BYTES = 600e6     # every stream of a per-kernel timing rotates over at least this many bytes of distinct buffers
+
+
+def cold_count(nbytes, at_least):
+    """Buffers of nbytes to rotate over so that this stream alone exceeds the 256 MB Infinity Cache more than twice:
+    a packed stream of a few megabytes would otherwise be served from that cache on every repetition (on the 302 MB
+    bf16 tensor, three rotating 4-bit payloads of 76 MB fit it and unpack read them at 0.90 of the HBM peak; with the
+    payloads cold it does not)."""
+    return max(at_least, int(-(-COLD_BYTES // nbytes)))
+
+
+def cold_payloads(qp, torch, x, q, n, bits, at_least):
+    """count distinct packed buffers holding the payload of x under q."""
+    first = qp.alloc_packed(n, bits)
+    qp.qp_quant_pack(x, q, first)
+    out = [first]
+    for _ in range(cold_count(first.numel(), at_least) - 1):
+        out.append(first.clone())
+    return out
+
+
 def hbm_entry(kernel, alg_bytes, us, traffic_ratio, source, timed):
     a = alg_bytes / us / 1e3
     return {"kernel": kernel, "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -224,13 +245,16 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
                          "HIP events around every search launch in an instrumented repetition of the timed steps")
     roofline["traffic_source"] = TRAFFIC_SOURCE["c2"]
 
-    rot = f"{args.kernel_reps} back-to-back launches over {NBUF} rotating buffer sets between two HIP events"
+    rot = (f"{args.kernel_reps} back-to-back launches between two HIP events, every stream rotating over at least {NBUF} distinct "
+           f"buffers and {COLD_BYTES / 1e6:.0f} MB")
     per_bits = {}
     for b in bits_set:
         q = qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)
         q = qp.qp_make_qparams((q.lo + q.hi) / 2, (q.hi - q.lo) / 2, b, n)
-        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % NBUF], q, packs[b][r % NBUF]))
-        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[b][r % NBUF], q, ys[r % NBUF]))
+        cold = cold_payloads(qp, torch, xs[0], q, n, b, NBUF)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % NBUF], q, cold[r % len(cold)]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(cold[r % len(cold)], q, ys[r % NBUF]))
+        del cold
         byts = in_bytes + n * b / 8
         per_bits[str(b)] = {"pack_us": tp, "pack_GBs": byts / tp / 1e3, "pack_frac_hbm": byts / tp / 1e3 / HBM_PEAK_GBS,
                             "unpack_us": tu, "unpack_GBs": byts / tu / 1e3,
@@ -307,10 +331,10 @@ def size_sweep(qp, torch, x_host, timed_reps):
         nb = max(3, 16 // m)
         xs = [torch.from_numpy(x_host).cuda().repeat(m) for _ in range(nb)]
         ys = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(nb)]
-        pk = [qp.alloc_packed(n, 4) for _ in range(nb)]
         q = qp.qp_make_qparams(0.0, 2.5, 4, n)
-        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, pk[r % nb]))
-        tu = timed_reps(lambda r: qp.qp_unpack_dequant(pk[r % nb], q, ys[r % nb]))
+        pk = cold_payloads(qp, torch, xs[0], q, n, 4, nb)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, pk[r % len(pk)]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(pk[r % len(pk)], q, ys[r % nb]))
         ws = qp.alloc_workspace(n)
         ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
         byts = n * 4 + n * 4 / 8
@@ -345,17 +369,18 @@ def c3_leg(qp, si, torch, timed_reps, reps):
     cfg.cands_per_round = 32
     ws = qp.alloc_workspace(n, cfg)
     st = qp.qp_stats(xs[0], ws)
-    rot = f"{reps} back-to-back launches over {nb} rotating buffer sets between two HIP events"
+    rot = (f"{reps} back-to-back launches between two HIP events, every stream rotating over at least {nb} distinct buffers "
+           f"and {COLD_BYTES / 1e6:.0f} MB")
     ts = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
     out = {"elements": n, "input": "fp32", "cands_per_round": 32, "buffers_rotated": nb,
            "roofline_stats": hbm_entry("k_stats_pass1 + k_stats_pass2", 2 * in_bytes, ts, None, None, rot), "per_bitwidth": {}}
     for b in si.CONFIG_BITS["C3"]:
-        packs = [qp.alloc_packed(n, b) for _ in range(nb)]
         res, q = qp.qp_dsaciq_search(xs[0], st, b, ws, cfg=cfg)
+        packs = cold_payloads(qp, torch, xs[0], q, n, b, nb)
         tsr = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], b, ws, cfg=cfg), 24)
-        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % nb]))
-        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % nb], q, ys[r % nb]))
-        tsend = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % nb], cfg=cfg), 24)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % len(packs)]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % len(packs)], q, ys[r % nb]))
+        tsend = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % len(packs)], cfg=cfg), 24)
         byts = in_bytes + n * b / 8
         out["per_bitwidth"][str(b)] = {
             "j_star": res.j_star, "mse_star_over_mse_aciq": res.mse_star / res.mse_aciq,
@@ -381,7 +406,8 @@ def large_tensor_leg(qp, si, torch, timed_reps, reps):
     for i in range(nb):
         ys[(i + 1) % nb].copy_(ys[i])
     st = qp.qp_stats(xs[0], ws)
-    rot = f"{reps} back-to-back launches over {nb} rotating buffer sets between two HIP events"
+    rot = (f"{reps} back-to-back launches between two HIP events, every stream rotating over at least {nb} distinct buffers "
+           f"and {COLD_BYTES / 1e6:.0f} MB")
     t_stats = timed_reps(lambda r: qp.qp_stats_async(xs[r % nb], ws))
     out = {"elements": n, "input": "bf16", "buffers_rotated": nb, "stats_us": t_stats,
            # a bf16 tensor of this size goes through its value table: ONE read of the tensor (2 B per element) instead of
@@ -392,12 +418,12 @@ def large_tensor_leg(qp, si, torch, timed_reps, reps):
     out["hbm_copy_reference_GBs"] = 2 * n * 4 / tcopy / 1e3   # plain device-to-device copy of the fp32 output tensor
     out["per_bitwidth"] = {}
     for b in si.CONFIG_BITS["C5"]:
-        packs = [qp.alloc_packed(n, b) for _ in range(nb)]
         res, q = qp.qp_dsaciq_search(xs[0], st, b, ws)
-        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % nb]))
-        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % nb], q, ys[r % nb]))
+        packs = cold_payloads(qp, torch, xs[0], q, n, b, nb)
+        tp = timed_reps(lambda r: qp.qp_quant_pack(xs[r % nb], q, packs[r % len(packs)]))
+        tu = timed_reps(lambda r: qp.qp_unpack_dequant(packs[r % len(packs)], q, ys[r % nb]))
         ts = timed_reps(lambda r: qp.qp_dsaciq_search_async(xs[r % nb], b, ws))
-        tsend = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % nb]))
+        tsend = timed_reps(lambda r: qp.qp_compress_async(xs[r % nb], b, ws, packs[r % len(packs)]))
         bp, bu = n * 2 + n * b / 8, n * 4 + n * b / 8
         out["per_bitwidth"][str(b)] = {
             "j_star": res.j_star,
