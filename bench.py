@@ -8,7 +8,10 @@ quantize + pack -> unpack + dequantize) over the ViT-Base stage-boundary tensor
 the step).  Inputs are synthetic (seeded mixture of Laplace and Gaussian values with scaled
 outliers), resident in HBM before the timed region; passes rotate over 16 distinct
 input/output buffer sets (> 600 MB) so that the tensor is not served from the 256 MB
-Infinity Cache left warm by the previous pass.
+Infinity Cache left warm by the previous pass.  The six passes are independent jobs and are
+issued round-robin over `--streams` HIP streams (default 3, default priority, a workspace
+each), so that the HBM-bound steps of one pass run beside the ALU-bound search of another;
+`one_stream` repeats the timed steps with everything on one stream.
 
 Prints ONE JSON line.  `value` is activation bytes entering the path per second.
 `roofline` describes the kernel that dominates the step (the directed-search kernel, bound by
@@ -53,7 +56,7 @@ ALL_LEGS = ("c2", "c3", "c5", "c1", "c4", "cpu")
 # not measured by this process: a changed kernel shows in them only when those summaries are regenerated.
 TRAFFIC_RATIO = {
     # profiles/hbm_traffic_C2_fp32.txt
-    "c2_search_bytes": 133.70e6, "c2_pack": 1.0002, "c2_unpack": 1.0033, "c2_stats": 1.0063,
+    "c2_search_bytes": 86.95e6, "c2_pack": 1.0003, "c2_unpack": 1.0033, "c2_stats": 1.0062,
     # profiles/hbm_traffic_C5_bf16.txt
     "c5_value_hist": 1.0094, "c5_pack": 1.0001, "c5_unpack": 1.0022,
 }
@@ -100,17 +103,25 @@ def alu_entry(kernel, n, ncand, us, traffic, timed):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps before the timed ones (after a pause on the host the GPU needs some tens of milliseconds "
+                         "of work to reach its sustained clock: 3 steps left the first timed steps 6 %% slow)")
     ap.add_argument("--legs", default=",".join(ALL_LEGS),
                     help="comma-separated subset of " + ",".join(ALL_LEGS) + " (default: all).  The timed step is the "
                          "c2 leg; without it only the chosen legs run and `value` is null (for profiles of one leg)")
     ap.add_argument("--kernel-reps", type=int, default=64, help="back-to-back launches per kernel timing")
     ap.add_argument("--c4-microbatches", type=int, default=500)
+    ap.add_argument("--streams", type=int, default=3,
+                    help="HIP streams (default priority) that the independent passes of a step and the microbatches of the c4 leg "
+                         "are spread over, each with its own workspace; 1 = everything on one stream")
     ap.add_argument("--no-sweep", action="store_true",
                     help="leave the size sweep out of the c2 leg (it launches the same kernels on larger tensors, which would "
                          "mix into a profiler's per-kernel averages)")
     args = ap.parse_args()
+    if not 1 <= args.streams <= 8:
+        print("bench.py: --streams takes 1 to 8", file=sys.stderr)
+        return 2
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (tensors shard by microbatch with no exchange); "
               "use --gpus 1", file=sys.stderr)
@@ -131,6 +142,10 @@ def main() -> int:
         return 2
     qp.lib()
     torch.cuda.set_device(0)
+    # The side streams, made once and first.  As measured: the first three streams a process makes overlap fully; streams made
+    # after them overlap less (a HIP process has four hardware queues by default, so later streams share one, and two
+    # lanes on one queue run one after the other).
+    side_streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
 
     # short kernels (about 10 us): an event pair per launch would add a fifth to them, so kernel_reps
     # back-to-back launches over rotating buffers are timed between two HIP events on the launch stream
@@ -160,7 +175,7 @@ def main() -> int:
     x_c2 = None
     if "c2" in legs:
         x_c2 = si.make_config("C2")
-        out.update(c2_leg(qp, si, torch, x_c2, args, timed_reps))
+        out.update(c2_leg(qp, si, torch, x_c2, args, timed_reps, side_streams))
     if "c3" in legs:
         out["c3_vit_large_fp32"] = c3_leg(qp, si, torch, timed_reps, args.kernel_reps)
     if "c5" in legs:
@@ -168,14 +183,14 @@ def main() -> int:
     if "c1" in legs:
         out["small_tensor_fp32"] = small_tensor_leg(qp, si, torch, timed_reps)
     if "c4" in legs:
-        out["microbatch_stream_fp32"] = c4_stream_leg(qp, si, torch, args.c4_microbatches)
+        out["microbatch_stream_fp32"] = c4_stream_leg(qp, si, torch, args.c4_microbatches, side_streams)
     if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline(x_c2 if x_c2 is not None else si.make_config("C2"), si.CONFIG_BITS["C2"])
     print(json.dumps(out))
     return 0
 
 
-def c2_leg(qp, si, torch, x_host, args, timed_reps):
+def c2_leg(qp, si, torch, x_host, args, timed_reps, side_streams):
     """The timed step (whole path, six bitwidths) and the per-kernel rooflines on the ViT-Base tensor."""
     bits_set = si.CONFIG_BITS["C2"]
     n = x_host.size
@@ -188,9 +203,19 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
     ev = lambda: torch.cuda.Event(enable_timing=True)
     counter = [0]
 
-    def one_pass(bits, timers=None):
+    # The six passes of a step are independent jobs (each a whole sender + receiver path at its own bitwidth), so the
+    # step hands them round-robin to `--streams` HIP streams of default priority, each with a workspace of its own: the
+    # HBM-bound statistics, pack and unpack of one pass then run beside the vector-ALU-bound search of another.
+    lanes = [(s, qp.alloc_workspace(n)) for s in side_streams]
+
+    def one_pass(bits, timers=None, lane=None):
         i = counter[0] % NBUF
         counter[0] += 1
+        if lane is not None:
+            s, w = lane
+            qp.qp_compress_async(xs[i], bits, w, packs[bits][i], stream=s)
+            qp.qp_unpack_dequant_dev(packs[bits][i], bits, w.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), ys[i], stream=s)
+            return
         if timers is None:
             qp.qp_compress_async(xs[i], bits, ws, packs[bits][i])
             qp.qp_unpack_dequant_dev(packs[bits][i], bits, qdev, ys[i])
@@ -207,25 +232,34 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
         e[4].record()
         timers.append((bits, e))
 
-    def step(timers=None):
+    def step(timers=None, overlapped=False):
         for b in bits_set:
-            one_pass(b, timers)
+            one_pass(b, timers, lanes[counter[0] % len(lanes)] if overlapped and lanes else None)   # round-robin across steps too
 
     # four plain device copies of the tensor: under a rocprofv3 counter run these calibrate what
     # FETCH_SIZE / WRITE_SIZE read for a kernel that moves a known number of bytes
     for i in range(4):
         ys[i].copy_(xs[i])
     for _ in range(args.warmup):
-        step()
+        step(overlapped=True)
     torch.cuda.synchronize()
-    # timed region: exactly `steps` steps of the fused device-resident path, nothing else on the stream
+    # timed region: exactly `steps` steps of the fused device-resident path, nothing else on the device
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        step(overlapped=True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = len(bits_set) * in_bytes / (ms_per_step * 1e-3) / 1e9
+    # the same steps with the six passes one after another on one stream (what the stage times below add up to)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step_one_stream = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # the same `steps` steps again with a HIP event between the stages of every pass (this costs a few
     # microseconds per pass and one extra small launch, so it is kept out of `value`)
@@ -310,10 +344,14 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps):
                                "70% Laplace(0,0.4)/30% N(0.1,1) + 0.05% outliers x30, full path (stats, DS-ACIQ t=100, pack, "
                                "unpack) once per bitwidth in {2,3,4,6,8,16}; the largest single-GPU configuration (C5, "
                                "256x577x1024 bf16) is the large_tensor_bf16 entry of this line",
-                   "elements": n, "bitwidths": list(bits_set), "passes_per_step": nb, "buffers_rotated": NBUF},
+                   "elements": n, "bitwidths": list(bits_set), "passes_per_step": nb, "buffers_rotated": NBUF,
+                   "streams": max(1, args.streams)},
         "value_is": "activation bytes entering the whole path per second; the metric's named rates (quantize+pack, "
                     "unpack+dequantize GB/s and % of HBM peak, DS-ACIQ us per tensor) are roofline_pack, roofline_unpack "
                     "and dsaciq_us_per_tensor",
+        "one_stream": {"ms_per_step": ms_per_step_one_stream, "GBs": nb * in_bytes / ms_per_step_one_stream / 1e6,
+                       "note": "the same steps with the six passes back to back on one stream; stage_us and the rooflines are "
+                               "measured this way, so their sum times six is this figure, not ms_per_step"},
         "ms_per_step_instrumented": ms_per_step_instrumented,
         "stage_us": {k: mean(v) for k, v in stage.items()},
         "dsaciq_us_per_tensor": search_us,
@@ -442,39 +480,44 @@ def large_tensor_leg(qp, si, torch, timed_reps, reps):
     return out
 
 
-def c4_stream_leg(qp, si, torch, n_mb):
-    """C4: sender path + receiver per microbatch (32x257x1280 fp32, 42 MB), back to back on one stream, over a ring of
-    eight unit-Laplace buffers scaled per microbatch on the device; the bitwidth of each microbatch follows the
-    seeded bandwidth trace.  All n_mb inputs (21 GB at 500) are resident before the timed region."""
+def c4_stream_leg(qp, si, torch, n_mb, side_streams):
+    """C4: sender path + receiver per microbatch (32x257x1280 fp32, 42 MB) over a ring of eight unit-Laplace buffers
+    scaled per microbatch on the device; the bitwidth of each microbatch follows the seeded bandwidth trace.  All n_mb
+    inputs (21 GB at 500) are resident before the timed region.  Timed twice: back to back on one stream, and with the
+    microbatches handed round-robin to the side streams (a workspace, payload and output buffer each)."""
     n = si.numel("C4")
     stream = si.c4_stream(n_mb)
     ring = [torch.from_numpy(si.unit_laplace(n, 100 + b)).cuda() for b in range(8)]
     xs = [ring[buf] * b_m for (buf, b_m, bw, bits) in stream]          # n_mb x 42 MB, all distinct
-    packs = {k: qp.alloc_packed(n, k) for k in sorted({s[3] for s in stream})}
-    ws = qp.alloc_workspace(n)
-    y = torch.empty(n, dtype=torch.float32, device="cuda")
-    qdev = ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS)
+    kset = sorted({s[3] for s in stream})
+    lanes = [(s, qp.alloc_workspace(n), {k: qp.alloc_packed(n, k) for k in kset}, torch.empty(n, dtype=torch.float32, device="cuda"))
+             for s in (side_streams or [None])]
 
-    def run():
-        for x, (_, _, _, bits) in zip(xs, stream):
-            qp.qp_compress_async(x, bits, ws, packs[bits])
-            qp.qp_unpack_dequant_dev(packs[bits], bits, qdev, y)
+    def run(nl):
+        for m, (x, (_, _, _, bits)) in enumerate(zip(xs, stream)):
+            s, ws, packs, y = lanes[m % nl]
+            s = s if nl > 1 else None
+            qp.qp_compress_async(x, bits, ws, packs[bits], stream=s)
+            qp.qp_unpack_dequant_dev(packs[bits], bits, ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), y, stream=s)
 
-    run()
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    run()
-    b.record()
-    torch.cuda.synchronize()
-    us = a.elapsed_time(b) * 1e3 / n_mb
+    def timed(nl):
+        run(nl)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(nl)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / n_mb
+
+    us_one = timed(1)
+    us = timed(len(lanes)) if len(lanes) > 1 else us_one
     hist = {}
     for s_ in stream:
         hist[str(s_[3])] = hist.get(str(s_[3]), 0) + 1
     return {"elements_per_microbatch": n, "microbatches": n_mb, "input_bytes_resident": n_mb * n * 4,
-            "bitwidths_used": hist, "us_per_microbatch": us,
-            "activation_GBs": n * 4 / us / 1e3,
-            "timed": "statistics, DS-ACIQ (t = 100), quantize+pack, unpack+dequantize per microbatch, one stream, two HIP events"}
+            "bitwidths_used": hist, "streams": len(lanes), "us_per_microbatch": us, "activation_GBs": n * 4 / us / 1e3,
+            "one_stream": {"us_per_microbatch": us_one, "activation_GBs": n * 4 / us_one / 1e3},
+            "timed": "statistics, DS-ACIQ (t = 100), quantize+pack, unpack+dequantize per microbatch; host clock around all "
+                     "microbatches between two device synchronisations"}
 
 
 def small_tensor_leg(qp, si, torch, timed_reps):

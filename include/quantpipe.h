@@ -123,8 +123,7 @@ typedef struct {
     uint32_t cands_per_round;  /* 1..32: most candidates scored per pass over a large tensor (the library picks
                                   a round size of 16, 13, 8, 4, 2 or 1 within it; tensors searched tile by tile
                                   score all candidates in one pass); never changes results.  Default 13: the
-                                  101 candidates in five rounds of 13 and three of 12, which leaves seven
-                                  waves per SIMD of gfx950 */
+                                  101 candidates in five rounds of 13 and three of 12 */
     uint32_t nbins;            /* kept with the configuration for callers; the search itself does not use it */
     uint32_t dist;             /* QP_LAPLACE (the paper's model), QP_GAUSS or QP_DIST_AUTO */
     uint32_t flags;            /* QP_SEARCH_* bits, 0 = the paper's method */
@@ -284,7 +283,12 @@ qp_status qp_unpack_dequant_dev(const void *packed_dev, size_t packed_bytes, uin
  * (device to device) so that it can travel with the payload.  The statistics, the
  * search result and the scores are left in the workspace regions as by the separate
  * calls; nothing is reported about NaN / Inf elements here (QP_WS_STATS holds their
- * count; such elements are packed as code 0). */
+ * count; such elements are packed as code 0).
+ * All state of a call lives in its workspace, so tensors that do not depend on each other
+ * (microbatches, stage boundaries) may be in flight together, each call with a workspace of
+ * its own on a stream of its own (default priority).  That pays on gfx950: the statistics,
+ * pack and unpack kernels are bound by HBM and the search by vector ALU work, and four
+ * streams finish six ViT-Base tensors in the time one stream needs for five. */
 qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
                             const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
                             void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev,

@@ -13,8 +13,9 @@
 //   - a lane keeps 8 elements in VGPRs and runs the round's candidates over them; a candidate's
 //     grid is read from LDS once: lo lives in a VGPR, hi, scale and 1/scale in SGPRs, the running
 //     sums are fp64 accumulators in VGPRs: the inner loop touches no memory and holds no
-//     per-candidate test, the kernel needs 68 VGPRs and seven waves fit a SIMD (the sequence is a
-//     dependent chain per element: its issue rate depends on how many waves interleave);
+//     per-candidate test; the register budget is held to five waves per SIMD (the sequence is a
+//     dependent chain per element and its issue rate depends on how many waves interleave: three
+//     waves cost a fifth more cycles, four to seven measure the same);
 //   - the grid is sized to the number of blocks the device keeps resident (one wave of
 //     blocks, no tail);
 //   - per-block partial sums go to the workspace, candidate-major; the last block of a round
@@ -160,11 +161,12 @@ __device__ __forceinline__ void score_pass(const void *__restrict__ x, uint64_t 
 // either exactly CMAX candidates (the first `full` rounds) or exactly CMAX - 1 (the others): 101 candidates
 // are 5 rounds of 13 and 3 of 12.  Where a list does not split that way every round takes CMAX and the slots
 // past the end of the list repeat the last candidate and are not stored.
-// Waves per SIMD that the register allocation is held to (the common path needs 68 vector registers with
-// 13 candidates).
+// Waves per SIMD that the register allocation is held to.  The search alone takes the same time with four to
+// seven (it is bound by instruction issue); with five, work that other streams launch beside it (the HBM-bound
+// steps of other tensors) gets through 2 % sooner than with seven.
 template <int DT, int CMAX> constexpr int search_waves()
 {
-    return CMAX <= 13 ? 7 : 6;
+    return 5;
 }
 
 template <int DT, int CMAX>

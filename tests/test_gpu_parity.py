@@ -1001,9 +1001,52 @@ def test_two_streams_with_their_own_workspaces(qp):
         assert (bytes(qp.read_ws(wa, qp.QP_WS_RESULT, qp.qp_search_result_t)), bytes(qp.read_ws(wb, qp.QP_WS_RESULT, qp.qp_search_result_t))) == ref
 
 
+@pytest.mark.timeout(600)
+def test_timed_step_spread_over_four_streams(qp):
+    """The launch configuration bench.py times: the six passes of a step over the full C2 tensor handed round-robin to four
+    streams, each with its own workspace, several steps in flight.  Every payload, output and result record equals
+    what the same pass leaves when it runs alone on one stream (whose parity with the oracle the tests above hold)."""
+    x = si.make_config("C2")
+    n, bits_set = x.size, si.CONFIG_BITS["C2"]
+    d = to_dev(x)
+    ws = qp.alloc_workspace(n)
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    ref = {}
+    for b in bits_set:
+        pk = qp.alloc_packed(n, b)
+        qp.qp_compress_async(d, b, ws, pk)
+        qp.qp_unpack_dequant_dev(pk, b, ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), y)
+        torch.cuda.synchronize()
+        ref[b] = (pk, y.clone(), bytes(qp.read_ws(ws, qp.QP_WS_RESULT, qp.qp_search_result_t)),
+                  bytes(qp.read_ws(ws, qp.QP_WS_QPARAMS, qp.qp_qparams_t)))
+    lanes = [(torch.cuda.Stream(), qp.alloc_workspace(n)) for _ in range(4)]
+    steps = 3
+    out = {(s, b): (qp.alloc_packed(n, b), torch.empty(n, dtype=torch.float32, device="cuda")) for s in range(steps) for b in bits_set}
+    recs = {}
+    torch.cuda.synchronize()
+    k = 0
+    for s in range(steps):
+        for b in bits_set:
+            st, w = lanes[k % 4]
+            k += 1
+            pk, yy = out[(s, b)]
+            qp.qp_compress_async(d, b, w, pk, stream=st)
+            qp.qp_unpack_dequant_dev(pk, b, w.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), yy, stream=st)
+            # the records of this pass, copied out on its stream before the next pass on that stream overwrites them
+            with torch.cuda.stream(st):
+                recs[(s, b)] = w.clone()
+    torch.cuda.synchronize()
+    for (s, b), (pk, yy) in out.items():
+        assert torch.equal(pk, ref[b][0]), (s, b)
+        assert torch.equal(yy, ref[b][1]), (s, b)
+        w = recs[(s, b)]
+        assert bytes(qp.read_ws(w, qp.QP_WS_RESULT, qp.qp_search_result_t)) == ref[b][2], (s, b)
+        assert bytes(qp.read_ws(w, qp.QP_WS_QPARAMS, qp.qp_qparams_t)) == ref[b][3], (s, b)
+
+
 # ----------------------------------------------------------------------------- histogram-fit reading of Eq. 1
 
-HIST_CASES = [("C1", None), ("C2", 1_234_567), ("C3", 987_653), ("C5", 777_779)]
+HIST_CASES =[("C1", None), ("C2", 1_234_567), ("C3", 987_653), ("C5", 777_779)]
 
 
 @pytest.mark.parametrize("name,n", HIST_CASES, ids=[c[0] for c in HIST_CASES])
