@@ -48,6 +48,7 @@ HBM_PEAK_GBS = 8000.0                  # MI355X HBM3E, published
 SEARCH_LANEOPS_PER_ELEM_CAND = 8       # algorithmic vector operations per element and candidate
 VALU_PEAK_TLANEOPS = 8.0 / (6.0 / 78.64 + 2.0 / 39.32)
 NBUF = 16
+PREHEAT_S = 0.05                       # of the timed step's own work before the warm-up steps, see c2_leg
 ALL_LEGS = ("c2", "c3", "c5", "c1", "c4", "cpu")
 
 # HBM traffic per launch as a multiple of the kernel's algorithmic bytes, from rocprofv3 --pmc FETCH_SIZE /
@@ -240,6 +241,12 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps, side_streams):
     # FETCH_SIZE / WRITE_SIZE read for a kernel that moves a known number of bytes
     for i in range(4):
         ys[i].copy_(xs[i])
+    # Steady-state clock first, whatever --warmup says: after a pause on the host the GPU needs some tens of milliseconds
+    # of work to reach the clock it then sustains (timed after 4 ms of work the same steps read 6 % slower).
+    t_heat = time.perf_counter() + PREHEAT_S
+    while time.perf_counter() < t_heat:
+        step(overlapped=True)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step(overlapped=True)
     torch.cuda.synchronize()
@@ -345,7 +352,7 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps, side_streams):
                                "unpack) once per bitwidth in {2,3,4,6,8,16}; the largest single-GPU configuration (C5, "
                                "256x577x1024 bf16) is the large_tensor_bf16 entry of this line",
                    "elements": n, "bitwidths": list(bits_set), "passes_per_step": nb, "buffers_rotated": NBUF,
-                   "streams": max(1, args.streams)},
+                   "streams": max(1, args.streams), "preheat_ms_before_warmup": PREHEAT_S * 1e3},
         "value_is": "activation bytes entering the whole path per second; the metric's named rates (quantize+pack, "
                     "unpack+dequantize GB/s and % of HBM peak, DS-ACIQ us per tensor) are roofline_pack, roofline_unpack "
                     "and dsaciq_us_per_tensor",
