@@ -182,7 +182,7 @@ def main() -> int:
     if "c5" in legs:
         out["large_tensor_bf16"] = large_tensor_leg(qp, si, torch, timed_reps, args.kernel_reps)
     if "c1" in legs:
-        out["small_tensor_fp32"] = small_tensor_leg(qp, si, torch, timed_reps)
+        out["small_tensor_fp32"] = small_tensor_leg(qp, si, torch, timed_reps, side_streams)
     if "c4" in legs:
         out["microbatch_stream_fp32"] = c4_stream_leg(qp, si, torch, args.c4_microbatches, side_streams)
     if "cpu" in legs:
@@ -527,7 +527,7 @@ def c4_stream_leg(qp, si, torch, n_mb, side_streams):
                      "microbatches between two device synchronisations"}
 
 
-def small_tensor_leg(qp, si, torch, timed_reps):
+def small_tensor_leg(qp, si, torch, timed_reps, side_streams):
     """C1: sender path (statistics, DS-ACIQ t = 100, quantize+pack) and its search alone on the 1x197x768 tensor,
     launched eagerly and replayed from a HIP graph that holds 16 sender paths over rotating inputs."""
     x = si.make_config("C1")
@@ -552,9 +552,56 @@ def small_tensor_leg(qp, si, torch, timed_reps):
             qp.qp_compress_async(xs[r % nb], 4, ws, packed)
     torch.cuda.synchronize()
     t_graph = timed_reps(lambda r: g.replay(), 16) / per_graph
-    return {"elements": n, "bits": 4, "dsaciq_us_per_tensor": t_search, "sender_path_us_per_tensor": t_send,
-            "sender_path_us_per_tensor_graph_replay": t_graph,
-            "timed": "back-to-back calls on one stream between two HIP events; graph: 16 replays of a HIP graph holding 16 sender paths"}
+    out = {"elements": n, "bits": 4, "dsaciq_us_per_tensor": t_search, "sender_path_us_per_tensor": t_send,
+           "sender_path_us_per_tensor_graph_replay": t_graph,
+           "timed": "back-to-back calls on one stream between two HIP events; graph: 16 replays of a HIP graph holding 16 sender paths"}
+    if side_streams:
+        # independent tensors in flight: the same sender paths handed round-robin to the side streams (a workspace and a
+        # payload buffer each); host clock around 3 x 256 tensors between two device synchronisations, best of three
+        lanes = [(st, qp.alloc_workspace(n), qp.alloc_packed(n, 4)) for st in side_streams]
+        per = 256
+
+        def burst():
+            for r in range(per):
+                st, w, pk = lanes[r % len(lanes)]
+                qp.qp_compress_async(xs[r % nb], 4, w, pk, stream=st)
+        burst()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            burst()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) * 1e6 / per
+            best = dt if best is None else min(best, dt)
+        out["sender_path_us_per_tensor_in_flight_on_side_streams"] = {"streams": len(lanes), "us_per_tensor": best}
+        # the same with one HIP graph of 16 sender paths per side stream, replayed side by side (the eager burst above is
+        # bound by the host's launch rate: five launches per tensor)
+        graphs = []
+        for st, w, pk in lanes:
+            gk = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gk, stream=st):
+                for r in range(per_graph):
+                    qp.qp_compress_async(xs[r % nb], 4, w, pk)
+            graphs.append((st, gk))
+        torch.cuda.synchronize()
+
+        def replay_all(rounds):
+            for _ in range(rounds):
+                for st, gk in graphs:
+                    with torch.cuda.stream(st):
+                        gk.replay()
+        replay_all(4)
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            replay_all(16)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) * 1e6 / (16 * len(graphs) * per_graph)
+            best = dt if best is None else min(best, dt)
+        out["sender_path_us_per_tensor_in_flight_graph_replay"] = {"streams": len(lanes), "us_per_tensor": best}
+    return out
 
 
 def cpu_baseline(x_host, bits_set):
