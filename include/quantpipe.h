@@ -287,7 +287,7 @@ qp_status qp_unpack_dequant_dev(const void *packed_dev, size_t packed_bytes, uin
  * All state of a call lives in its workspace, so tensors that do not depend on each other
  * (microbatches, stage boundaries) may be in flight together, each call with a workspace of
  * its own on a stream of its own (default priority).  That pays on gfx950: the statistics,
- * pack and unpack kernels are bound by HBM and the search by vector ALU work, and four
+ * pack and unpack kernels are bound by HBM and the search by vector ALU work, and three
  * streams finish six ViT-Base tensors in the time one stream needs for five. */
 qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits,
                             const qp_search_cfg_t *cfg, void *ws_dev, size_t ws_bytes,
