@@ -23,6 +23,12 @@ constexpr uint32_t kNumValues16 = 65536;   // bit patterns of a bfloat16
 #define QP_VALUE_TABLE_MIN_N (1ull << 20)
 #endif
 constexpr uint64_t kValueTableMinN = QP_VALUE_TABLE_MIN_N;
+// Tensors at least this large take the forms of quantize+pack (3 and 6 bit) and unpack+dequantize that pay on
+// large tensors only (measured break-even between 9.7 M and 77 M elements).
+#ifndef QP_LARGE_FORMS_MIN_N
+#define QP_LARGE_FORMS_MIN_N (1ull << 24)
+#endif
+constexpr uint64_t kLargeFormsMinN = QP_LARGE_FORMS_MIN_N;
 
 // Per-block partial of the first statistics pass.
 struct Part1 {

@@ -10,7 +10,11 @@
 //   stage 2  the LDS tile is (k = 2,4,8,16) already the output byte stream, or (k = 3,6) an
 //            array of 12/24-bit chunks that eight/four at a time squeeze into three dwords;
 //            lanes read it back 16 bytes at a time and store 128-bit (k = 3,6: 96-bit)
-//            words, consecutive lanes to consecutive addresses.
+//            words, consecutive lanes to consecutive addresses.  For k = 3,6 on tensors of 2^24
+//            elements or more (RESTAGE) the three dwords go back to LDS first and leave as
+//            128-bit words like the others: 8-10 % faster there (151 M bf16 elements: 64.9 ->
+//            58.3 us at 3 bit, 71.2 -> 65.8 us at 6 bit), 2-4 % slower on a 9.7 M-element
+//            tensor, where the extra barrier shows.
 // So both the loads and the stores of a wave are contiguous, and the bit-packing is a
 // cooperative transpose through LDS rather than per-lane strided access.  Loads and stores
 // are nontemporal (the tensor and the payload are touched once); measured on MI355X that is
@@ -59,7 +63,21 @@ __device__ __forceinline__ void squeeze24(uint32_t w0, uint32_t w1, uint32_t w2,
     o[2] = (w2 >> 16) | (w3 << 8);
 }
 
-template <int K, int DT>
+// one group: K = 3, eight 12-bit chunks (one per 16-bit LDS slot); K = 6, four 24-bit chunks -> three dwords
+template <int K> __device__ __forceinline__ void squeeze_group(const uint4 a, uint32_t (&o)[3])
+{
+    if constexpr (K == 3) {
+        const uint32_t w0 = (a.x & 0xfffu) | ((a.x >> 16) << 12);
+        const uint32_t w1 = (a.y & 0xfffu) | ((a.y >> 16) << 12);
+        const uint32_t w2 = (a.z & 0xfffu) | ((a.z >> 16) << 12);
+        const uint32_t w3 = (a.w & 0xfffu) | ((a.w >> 16) << 12);
+        squeeze24(w0, w1, w2, w3, o);
+    } else {
+        squeeze24(a.x, a.y, a.z, a.w, o);
+    }
+}
+
+template <int K, int DT, bool RESTAGE>
 __global__ __launch_bounds__(kPkThreads) void k_quant_pack(const void *__restrict__ x, uint64_t n, Grid4 g,
                                                            const qp_qparams_t *__restrict__ qdev,
                                                            uint32_t *__restrict__ out, uint64_t ndw)
@@ -109,21 +127,12 @@ __global__ __launch_bounds__(kPkThreads) void k_quant_pack(const void *__restric
     // ---- stage 2 ----
     constexpr uint32_t tile_dw = kPkTile * K / 32;           // dwords of output per tile
     const uint64_t d0 = (uint64_t)blockIdx.x * tile_dw;
-    if constexpr (K == 3 || K == 6) {
+    if constexpr ((K == 3 || K == 6) && !RESTAGE) {
         // groups of three dwords: K = 3 from eight 12-bit chunks, K = 6 from four 24-bit chunks
         constexpr uint32_t groups = tile_dw / 3;               // 128 (K = 3) or 256 (K = 6)
         for (uint32_t gi = tid; gi < groups; gi += kPkThreads) {
-            const uint4 a = reinterpret_cast<const uint4 *>(lds)[gi];
             uint32_t o[3];
-            if constexpr (K == 3) {
-                const uint32_t w0 = (a.x & 0xfffu) | ((a.x >> 16) << 12);
-                const uint32_t w1 = (a.y & 0xfffu) | ((a.y >> 16) << 12);
-                const uint32_t w2 = (a.z & 0xfffu) | ((a.z >> 16) << 12);
-                const uint32_t w3 = (a.w & 0xfffu) | ((a.w >> 16) << 12);
-                squeeze24(w0, w1, w2, w3, o);
-            } else {
-                squeeze24(a.x, a.y, a.z, a.w, o);
-            }
+            squeeze_group<K>(reinterpret_cast<const uint4 *>(lds)[gi], o);
             const uint64_t d = d0 + 3ull * gi;
             if (d + 3 <= ndw) {
                 uint32_t *p = out + d;
@@ -136,6 +145,30 @@ __global__ __launch_bounds__(kPkThreads) void k_quant_pack(const void *__restric
             }
         }
     } else {
+        if constexpr (K == 3 || K == 6) {
+            // A lane squeezes its one or two groups in registers; once every lane has read its chunks the dwords
+            // go back to LDS, where they form the tile's output byte stream as for the other bitwidths.
+            constexpr uint32_t groups = tile_dw / 3;           // 128 ... 512
+            constexpr int GPL = (groups + kPkThreads - 1) / kPkThreads;
+            uint32_t o[GPL][3];
+#pragma unroll
+            for (int i = 0; i < GPL; ++i) {
+                const uint32_t gi = tid + (uint32_t)i * kPkThreads;
+                if (gi < groups) squeeze_group<K>(reinterpret_cast<const uint4 *>(lds)[gi], o[i]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < GPL; ++i) {
+                const uint32_t gi = tid + (uint32_t)i * kPkThreads;
+                if (gi < groups) {
+                    uint32_t *w = reinterpret_cast<uint32_t *>(lds) + 3u * gi;
+                    w[0] = o[i][0];
+                    w[1] = o[i][1];
+                    w[2] = o[i][2];
+                }
+            }
+            __syncthreads();
+        }
         constexpr uint32_t quads = tile_dw / 4;                // 16-byte words of output per tile
         for (uint32_t qi = tid; qi < quads; qi += kPkThreads) {
             const uint4 a = reinterpret_cast<const uint4 *>(lds)[qi];
@@ -152,21 +185,27 @@ __global__ __launch_bounds__(kPkThreads) void k_quant_pack(const void *__restric
     }
 }
 
+template <int K, int DT, bool RESTAGE>
+static hipError_t launch_form(const void *x, uint64_t n, Grid4 g, const qp_qparams_t *qdev, void *packed, hipStream_t s)
+{
+    const uint64_t ndw = (n * K + 31) / 32;
+    const uint32_t blocks = ceil_div_u64(n, PackTile<DT>::elems);
+    hipLaunchKernelGGL((k_quant_pack<K, DT, RESTAGE>), dim3(blocks), dim3(kPkThreads), 0, s, x, n, g, qdev,
+                       static_cast<uint32_t *>(packed), ndw);
+    return hipGetLastError();
+}
+
 template <int K>
 static hipError_t launch_k(const void *x, uint64_t n, int dtype, Grid4 g, const qp_qparams_t *qdev, void *packed,
                            hipStream_t s)
 {
-    const uint64_t ndw = (n * K + 31) / 32;
-    if (dtype == QP_F32) {
-        const uint32_t blocks = ceil_div_u64(n, PackTile<QP_F32>::elems);
-        hipLaunchKernelGGL((k_quant_pack<K, QP_F32>), dim3(blocks), dim3(kPkThreads), 0, s, x, n, g, qdev,
-                           static_cast<uint32_t *>(packed), ndw);
-    } else {
-        const uint32_t blocks = ceil_div_u64(n, PackTile<QP_BF16>::elems);
-        hipLaunchKernelGGL((k_quant_pack<K, QP_BF16>), dim3(blocks), dim3(kPkThreads), 0, s, x, n, g, qdev,
-                           static_cast<uint32_t *>(packed), ndw);
+    if constexpr (K == 3 || K == 6) {
+        if (n >= kLargeFormsMinN)
+            return dtype == QP_F32 ? launch_form<K, QP_F32, true>(x, n, g, qdev, packed, s)
+                                   : launch_form<K, QP_BF16, true>(x, n, g, qdev, packed, s);
     }
-    return hipGetLastError();
+    return dtype == QP_F32 ? launch_form<K, QP_F32, false>(x, n, g, qdev, packed, s)
+                           : launch_form<K, QP_BF16, false>(x, n, g, qdev, packed, s);
 }
 
 hipError_t launch_quant_pack(const void *x, uint64_t n, int dtype, uint32_t bits, const qp_qparams_t *hq,

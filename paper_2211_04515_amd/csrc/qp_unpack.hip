@@ -20,7 +20,6 @@ namespace qp {
 // write stream idle for longer; equal or slightly slower on 10 M elements) and for 6-bit codes at any size.
 struct UpSmall { static constexpr int threads = 256, stores = 4; };
 struct UpLarge { static constexpr int threads = 512, stores = 2; };
-constexpr uint64_t kUpLargeFrom = 1ull << 24;
 
 struct Deq {
     float lo, scale;
@@ -120,7 +119,7 @@ static hipError_t launch_shape(const void *packed, Deq q, const qp_qparams_t *qd
 template <int K>
 static hipError_t launch_k(const void *packed, Deq q, const qp_qparams_t *qdev, float *y, uint64_t n, hipStream_t s)
 {
-    if (n >= kUpLargeFrom || K == 6) return launch_shape<K, UpLarge>(packed, q, qdev, y, n, s);
+    if (n >= kLargeFormsMinN || K == 6) return launch_shape<K, UpLarge>(packed, q, qdev, y, n, s);
     return launch_shape<K, UpSmall>(packed, q, qdev, y, n, s);
 }
 

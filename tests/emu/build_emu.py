@@ -2,8 +2,8 @@
 runtime (tests/emu/hip/hip_runtime.h) with AddressSanitizer and UBSan, into tests/emu/_build/<tag>/emu_driver.
 
 Three builds: "default" (the library's own size thresholds: small tensors take the tile search),
-"streaming" (thresholds lowered so that tiny tensors take the streaming search and, for bf16, the value
-table) and "streaming_c2f" (as "streaming", plus the coarse-to-fine sweeps on the streaming kernel, which the
+"streaming" (thresholds lowered so that tiny tensors take the streaming search, for bf16 the value
+table, and from 2048 elements on the large-tensor forms of quantize+pack and unpack+dequantize) and "streaming_c2f" (as "streaming", plus the coarse-to-fine sweeps on the streaming kernel, which the
 library itself never launches).  Returns None when no host clang++ with C++20 is available."""
 from __future__ import annotations
 
@@ -18,11 +18,12 @@ ROOT = os.path.dirname(os.path.dirname(HERE))
 CSRC = os.path.join(ROOT, "paper_2211_04515_amd", "csrc")
 VARIANTS = {
     "default": [],
-    "streaming": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096", "-DQP_SEARCH_FILL_BLOCKS=8"],
+    "streaming": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096", "-DQP_SEARCH_FILL_BLOCKS=8",
+                  "-DQP_LARGE_FORMS_MIN_N=2048"],
     # as "streaming", and a coarse-to-fine search runs its two sweeps on the streaming kernel: the sequence that
     # the library refuses because its only GPU run faulted (the macro exists for this build alone)
     "streaming_c2f": ["-DQP_TILE_SEARCH_MAX_N=0", "-DQP_VALUE_TABLE_MIN_N=4096", "-DQP_SEARCH_FILL_BLOCKS=8",
-                      "-DQP_EMULATE_STREAMING_C2F=1"],
+                      "-DQP_LARGE_FORMS_MIN_N=2048", "-DQP_EMULATE_STREAMING_C2F=1"],
 }
 
 

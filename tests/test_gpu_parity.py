@@ -446,6 +446,31 @@ def test_pack_degenerate_grid(qp, bits):
     assert bool((y == 0.5).all())
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("kind", ["fp32", "bf16"])
+@pytest.mark.parametrize("n", [(1 << 24) - 3, (1 << 24) + 4099])
+def test_pack_and_unpack_forms_around_two_to_the_24(qp, kind, n):
+    """From 2^24 elements on the launchers take other forms of the same kernels (3- and 6-bit quantize+pack restaged
+    through LDS, 512-lane unpack): every bitwidth on both sides of the threshold, whole stream against the oracle."""
+    x = si.make_config("C5" if kind == "bf16" else "C2", n=n)
+    xf = as_f32(x)
+    xd = to_dev(x)
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    for bits in BITS:
+        oq = orc.make_qparams(0.03, 1.9, bits, n)
+        q = qp.qp_make_qparams(0.03, 1.9, bits, n)
+        assert (q.lo, q.hi, q.scale, q.inv_scale) == (oq.lo, oq.hi, oq.scale, oq.inv_scale)
+        packed = qp.alloc_packed(n, bits)
+        packed.fill_(0xA5)
+        qp.qp_quant_pack(xd, q, packed)
+        codes = orc.quantize(xf, oq)
+        assert np.array_equal(packed.cpu().numpy(), orc.pack(codes, bits)), bits
+        y.fill_(float("nan"))
+        qp.qp_unpack_dequant(packed, q, y)
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(codes, oq)), bits
+        del packed
+
+
 def test_device_resident_path_matches_host_path(qp):
     x = si.make_config("C3", n=500_009)
     xd = to_dev(x)
