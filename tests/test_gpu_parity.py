@@ -927,6 +927,31 @@ def test_sender_path_sizes(qp, n):
         check_sender_result(qp, x, bits, ws, packed)
 
 
+def test_sender_and_receiver_on_random_sizes(qp):
+    """Forty seeded random cases: size log-uniform in [1, 3 M] (so the tile search, the streaming search and, for bf16,
+    the value table all occur), fp32 or bf16, any bitwidth, a random location and scale."""
+    rng = np.random.default_rng(20221108)
+    for case in range(40):
+        n = int(np.exp(rng.uniform(0.0, np.log(3.0e6))))
+        bits = int(rng.choice(BITS))
+        bf16 = bool(rng.integers(0, 2))
+        loc, scale = float(rng.normal(0.0, 2.0)), float(np.exp(rng.uniform(np.log(1e-3), np.log(50.0))))
+        x32 = (si.unit_laplace(n, seed=1000 + case) * np.float32(scale) + np.float32(loc)).astype(np.float32)
+        x = si.f32_to_bf16_bits(x32) if bf16 else x32
+        print(f"[case] random #{case}: n={n} bits={bits} bf16={bf16} loc={loc:.3g} scale={scale:.3g}", flush=True)
+        xd = to_dev(x)
+        ws = qp.alloc_workspace(n)
+        ws.fill_(0xC3)
+        packed = qp.alloc_packed(n, bits)
+        qp.qp_compress_async(xd, bits, ws, packed)
+        torch.cuda.synchronize()
+        st, res, q = check_sender_result(qp, x, bits, ws, packed)
+        y = torch.empty(n, dtype=torch.float32, device="cuda")
+        qp.qp_unpack_dequant_dev(packed, bits, ws.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), y)
+        oq = oracle_q_from(q)
+        assert np.array_equal(y.cpu().numpy(), orc.dequantize(orc.quantize(as_f32(x), oq), oq)), case
+
+
 def test_sender_path_other_grids(qp):
     x = si.make_config("C2", n=200_003)
     xd = to_dev(x)
