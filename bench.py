@@ -353,7 +353,8 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps, side_streams):
                                "256x577x1024 bf16) is the large_tensor_bf16 entry of this line",
                    "elements": n, "bitwidths": list(bits_set), "passes_per_step": nb, "buffers_rotated": NBUF,
                    "streams": max(1, args.streams), "preheat_ms_before_warmup": PREHEAT_S * 1e3},
-        "value_is": "activation bytes entering the whole path per second; the metric's named rates (quantize+pack, "
+        "value_is": "activation bytes entering the whole path per second, the six independent passes of a step in flight on "
+                    "config.streams streams (one_stream: the same with one pass after the other); the metric's named rates (quantize+pack, "
                     "unpack+dequantize GB/s and % of HBM peak, DS-ACIQ us per tensor) are roofline_pack, roofline_unpack "
                     "and dsaciq_us_per_tensor",
         "one_stream": {"ms_per_step": ms_per_step_one_stream, "GBs": nb * in_bytes / ms_per_step_one_stream / 1e6,
