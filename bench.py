@@ -205,18 +205,14 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps, side_streams):
     counter = [0]
 
     # The six passes of a step are independent jobs (each a whole sender + receiver path at its own bitwidth), so the
-    # step hands them round-robin to `--streams` HIP streams of default priority, each with a workspace of its own: the
-    # HBM-bound statistics, pack and unpack of one pass then run beside the vector-ALU-bound search of another.
+    # step hands them round-robin to `--streams` HIP streams of default priority, each with a workspace of its own
+    # (qp_compress_many_async): the HBM-bound statistics, pack and unpack of one pass then run beside the
+    # vector-ALU-bound search of another.
     lanes = [(s, qp.alloc_workspace(n)) for s in side_streams]
 
-    def one_pass(bits, timers=None, lane=None):
+    def one_pass(bits, timers=None):
         i = counter[0] % NBUF
         counter[0] += 1
-        if lane is not None:
-            s, w = lane
-            qp.qp_compress_async(xs[i], bits, w, packs[bits][i], stream=s)
-            qp.qp_unpack_dequant_dev(packs[bits][i], bits, w.data_ptr() + qp.qp_ws_offset(qp.QP_WS_QPARAMS), ys[i], stream=s)
-            return
         if timers is None:
             qp.qp_compress_async(xs[i], bits, ws, packs[bits][i])
             qp.qp_unpack_dequant_dev(packs[bits][i], bits, qdev, ys[i])
@@ -233,9 +229,22 @@ def c2_leg(qp, si, torch, x_host, args, timed_reps, side_streams):
         e[4].record()
         timers.append((bits, e))
 
+    qrecs = torch.zeros(32 * len(bits_set), dtype=torch.uint8, device="cuda")   # the grid record that travels with each payload
+
+    def step_in_flight():
+        # sender side: one call, job k on lane k mod len(lanes); receiver side: each payload's unpack behind it on its lane
+        ii = [(counter[0] + k) % NBUF for k in range(len(bits_set))]
+        counter[0] += len(bits_set)
+        qp.qp_compress_many_async([(xs[i], b, packs[b][i], qrecs.data_ptr() + 32 * k) for k, (b, i) in enumerate(zip(bits_set, ii))],
+                                  [(w, s) for s, w in lanes])
+        for k, (b, i) in enumerate(zip(bits_set, ii)):
+            qp.qp_unpack_dequant_dev(packs[b][i], b, qrecs.data_ptr() + 32 * k, ys[i], stream=lanes[k % len(lanes)][0])
+
     def step(timers=None, overlapped=False):
+        if overlapped and lanes:
+            return step_in_flight()
         for b in bits_set:
-            one_pass(b, timers, lanes[counter[0] % len(lanes)] if overlapped and lanes else None)   # round-robin across steps too
+            one_pass(b, timers)
 
     # four plain device copies of the tensor: under a rocprofv3 counter run these calibrate what
     # FETCH_SIZE / WRITE_SIZE read for a kernel that moves a known number of bytes

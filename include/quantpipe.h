@@ -294,6 +294,37 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
                             void *packed_dev, size_t packed_bytes, qp_qparams_t *qparams_out_dev,
                             void *stream);
 
+/* ---- several tensors in flight --------------------------------------------------
+ * The tensors that cross stage boundaries (Sec. 3: one activation tensor per microbatch and
+ * boundary) do not depend on each other, so their sender paths may overlap.  Job i runs as
+ * qp_compress_async on lane i mod n_lanes, i.e. on that lane's stream with that lane's workspace;
+ * jobs of one lane follow each other in stream order, lanes run side by side.  On gfx950 three
+ * lanes hide the HBM-bound statistics and pack kernels of one tensor behind the ALU-bound search
+ * of another.  Every argument of every job is checked before the first kernel is launched (the
+ * errors are those of qp_compress_async; also QP_EINVAL if two lanes' workspaces overlap, if
+ * n_lanes is 0 or above 64, or if qparams_out_dev is NULL for a job whose lane a later job of the
+ * same call reuses: that later job overwrites the lane's records, so the grid must leave the
+ * workspace with the payload).  A lane's workspace holds the records of its last job afterwards.
+ * Streams are the caller's (default priority; two lanes may name the same stream and then run in
+ * order); the library creates none and allocates nothing.  A HIP error part of the way leaves the
+ * earlier jobs enqueued. */
+typedef struct {
+    const void   *x_dev;            /* n elements of dtype, 16-byte aligned */
+    uint64_t      n;
+    uint32_t      dtype;            /* qp_dtype */
+    uint32_t      bits;
+    void         *packed_dev;       /* 16-byte aligned */
+    uint64_t      packed_bytes;     /* >= qp_packed_bytes(n, bits) */
+    qp_qparams_t *qparams_out_dev;  /* 32 bytes of device memory, or NULL (see above) */
+} qp_job_t;
+typedef struct {
+    void  *ws_dev;                  /* >= qp_workspace_bytes(n, cfg) for every job of the lane */
+    size_t ws_bytes;
+    void  *stream;                  /* hipStream_t */
+} qp_lane_t;
+qp_status qp_compress_many_async(const qp_job_t *jobs, uint32_t count, const qp_search_cfg_t *cfg,
+                                 const qp_lane_t *lanes, uint32_t n_lanes);
+
 /* ---- the same sender path for callers that cannot allocate -----------------------
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
  * callers that cannot bring a workspace.  Same kernels and same results as qp_compress_async, with

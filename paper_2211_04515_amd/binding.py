@@ -12,14 +12,14 @@ import os
 import torch  # noqa: F401  (must precede CDLL: one HIP runtime per process)
 
 __all__ = [
-    "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS", "QP_DIST_AUTO", "QP_WS_MODEL", "qp_model_fit_t", "qp_model_fit", "qp_model_fit_async",
+    "QP_OK", "QP_EINVAL", "QP_ENOSPC", "QP_EHIP", "QP_ENONFINITE", "QP_F32", "QP_BF16", "QP_LAPLACE", "QP_GAUSS", "QP_DIST_AUTO", "QP_WS_MODEL", "qp_model_fit_t", "qp_model_fit", "qp_model_fit_async", "qp_job_t", "qp_lane_t",
     "QP_SEARCH_CLIP_TO_DATA", "QP_SEARCH_COARSE_TO_FINE", "QP_SEARCH_LOW_BITS_ONLY",
     "QP_WS_STATS", "QP_WS_RESULT", "QP_WS_QPARAMS", "QP_WS_HIST", "QP_WS_CANDS", "QP_WS_SCORES",
     "qp_stats_t", "qp_qparams_t", "qp_search_cfg_t", "qp_search_result_t", "qp_controller_t", "QuantPipeError", "BITS",
     "lib", "qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
     "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
     "qp_dsaciq_search_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant", "qp_unpack_dequant_dev",
-    "qp_compress_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
+    "qp_compress_async", "qp_compress_many_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update", "qp_strerror", "alloc_workspace", "alloc_packed", "dtype_of", "read_ws",
 ]
 
 QP_OK, QP_EINVAL, QP_ENOSPC, QP_EHIP, QP_ENONFINITE = 0, -1, -2, -3, -4
@@ -62,6 +62,15 @@ class qp_search_result_t(C.Structure):
 
 class qp_model_fit_t(C.Structure):
     _fields_ = [("fit_laplace", C.c_double), ("fit_gauss", C.c_double), ("dist", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class qp_job_t(C.Structure):
+    _fields_ = [("x_dev", C.c_void_p), ("n", C.c_uint64), ("dtype", C.c_uint32), ("bits", C.c_uint32),
+                ("packed_dev", C.c_void_p), ("packed_bytes", C.c_uint64), ("qparams_out_dev", C.c_void_p)]
+
+
+class qp_lane_t(C.Structure):
+    _fields_ = [("ws_dev", C.c_void_p), ("ws_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class QuantPipeError(RuntimeError):
@@ -108,6 +117,7 @@ def lib():
             "qp_unpack_dequant_dev": (i32, [vp, sz, u32, vp, vp, u64, vp]),
             "qp_compress_async": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, sz, vp, vp]),
             "qp_compress_noalloc": (i32, [vp, u64, i32, u32, C.POINTER(qp_search_cfg_t), vp, sz, vp, vp]),
+            "qp_compress_many_async": (i32, [C.POINTER(qp_job_t), u32, C.POINTER(qp_search_cfg_t), C.POINTER(qp_lane_t), u32]),
             "qp_next_bits": (i32, [C.c_double, u32, C.c_double, C.c_double, C.c_double, C.POINTER(u32)]),
             "qp_controller_init": (i32, [C.POINTER(qp_controller_t), u32, C.c_double, C.c_double, u32]),
             "qp_controller_update": (i32, [C.POINTER(qp_controller_t), C.c_double, C.c_double, C.POINTER(u32)]),
@@ -124,7 +134,7 @@ def lib():
 EXPORTS = ("qp_packed_bytes", "qp_workspace_bytes", "qp_ws_offset", "qp_default_search_cfg", "qp_stats",
            "qp_stats_async", "qp_aciq_alpha", "qp_aciq_constant", "qp_make_qparams", "qp_make_qparams_clipped", "qp_dsaciq_search",
            "qp_dsaciq_search_async", "qp_model_fit", "qp_model_fit_async", "qp_dsaciq_hist_search", "qp_dsaciq_hist_search_async", "qp_quant_pack", "qp_quant_pack_dev", "qp_unpack_dequant",
-           "qp_unpack_dequant_dev", "qp_compress_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update",
+           "qp_unpack_dequant_dev", "qp_compress_async", "qp_compress_many_async", "qp_compress_noalloc", "qp_next_bits", "qp_controller_init", "qp_controller_update",
            "qp_strerror")
 
 
@@ -284,6 +294,18 @@ def qp_compress_async(x, bits: int, ws, packed, qparams_out_dev_ptr: int = 0, cf
                                    _dev(packed), packed.numel() * packed.element_size(),
                                    C.c_void_p(qparams_out_dev_ptr) if qparams_out_dev_ptr else None,
                                    _stream(stream)), "qp_compress_async")
+
+
+def qp_compress_many_async(jobs, lanes, cfg=None) -> None:
+    """jobs: sequence of (x, bits, packed, qparams_out_dev_ptr or 0); lanes: sequence of (workspace, stream)."""
+    ja = (qp_job_t * len(jobs))()
+    for k, (x, bits, packed, qptr) in enumerate(jobs):
+        ja[k] = qp_job_t(x.data_ptr(), x.numel(), dtype_of(x), int(bits), packed.data_ptr(),
+                         packed.numel() * packed.element_size(), qptr or None)
+    la = (qp_lane_t * len(lanes))()
+    for k, (ws, stream) in enumerate(lanes):
+        la[k] = qp_lane_t(ws.data_ptr(), ws.numel(), _stream(stream).value)
+    _check(lib().qp_compress_many_async(ja, len(jobs), _cfgp(cfg), la, len(lanes)), "qp_compress_many_async")
 
 
 def qp_compress_noalloc(x, bits: int, packed, qparams_out_dev_ptr: int, cfg=None, stream=None) -> None:

@@ -365,9 +365,9 @@ qp_status qp_unpack_dequant_dev(const void *packed_dev, size_t packed_bytes, uin
     return unpack_common(packed_dev, packed_bytes, bits, nullptr, qparams_dev, y_dev, n, stream);
 }
 
-qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_search_cfg_t *cfg,
-                            void *ws_dev, size_t ws_bytes, void *packed_dev, size_t packed_bytes,
-                            qp_qparams_t *qparams_out_dev, void *stream)
+// Everything qp_compress_async refuses, before anything is launched.
+static qp_status check_compress(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_search_cfg_t *cfg,
+                                void *ws_dev, size_t ws_bytes, void *packed_dev, size_t packed_bytes)
 {
     if (!packed_dev || !bits_ok(bits) || !aligned16(packed_dev)) return QP_EINVAL;
     if (packed_bytes < qp_packed_bytes(n, bits)) return QP_ENOSPC;
@@ -375,12 +375,21 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
     if (!x_dev || n == 0 || n > kMaxN || !dtype_ok(dtype) || nbins < 16 || nbins > kMaxBins || !aligned16(x_dev))
         return QP_EINVAL;
     if (check_cfg(cfg) != QP_OK) return QP_EINVAL;
-    qp_status st = check_ws(n, cfg, ws_dev, ws_bytes);
+    const qp_status st = check_ws(n, cfg, ws_dev, ws_bytes);
     if (st != QP_OK) return st;
-    {   // refuse what the search would refuse before anything is launched
-        const SearchPlan plan = make_plan(bits, cfg);
-        if (!plan.aciq_only && plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;
-    }
+    // what the search would refuse
+    const SearchPlan plan = make_plan(bits, cfg);
+    if (!plan.aciq_only && plan.stride > 1u && !coarse_to_fine_supported(n, dtype, plan)) return QP_EINVAL;
+    return QP_OK;
+}
+
+qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint32_t bits, const qp_search_cfg_t *cfg,
+                            void *ws_dev, size_t ws_bytes, void *packed_dev, size_t packed_bytes,
+                            qp_qparams_t *qparams_out_dev, void *stream)
+{
+    qp_status st = check_compress(x_dev, n, dtype, bits, cfg, ws_dev, ws_bytes, packed_dev, packed_bytes);
+    if (st != QP_OK) return st;
+    const uint32_t nbins = (cfg && cfg->nbins) ? cfg->nbins : 2048u;
     // The two statistics passes leave partials and the search finalizes them itself; a large bf16 tensor goes
     // through its value table instead, which the statistics build and finalize and the search then reuses.
     // (With the model chosen on the device the record is needed before the search starts: the statistics finalize it.)
@@ -397,6 +406,40 @@ qp_status qp_compress_async(const void *x_dev, uint64_t n, qp_dtype dtype, uint3
         hipMemcpyAsync(qparams_out_dev, qdev, sizeof(qp_qparams_t), hipMemcpyDeviceToDevice,
                        static_cast<hipStream_t>(stream)) != hipSuccess)
         return QP_EHIP;
+    return QP_OK;
+}
+
+qp_status qp_compress_many_async(const qp_job_t *jobs, uint32_t count, const qp_search_cfg_t *cfg, const qp_lane_t *lanes,
+                                 uint32_t n_lanes)
+{
+    if (!jobs || !lanes || count == 0 || n_lanes == 0 || n_lanes > 64u) return QP_EINVAL;
+    // lanes must not share workspace memory (their calls overlap in time)
+    for (uint32_t a = 0; a < n_lanes; ++a) {
+        if (!lanes[a].ws_dev) return QP_EINVAL;
+        const char *a0 = static_cast<const char *>(lanes[a].ws_dev), *a1 = a0 + lanes[a].ws_bytes;
+        for (uint32_t b = a + 1; b < n_lanes; ++b) {
+            const char *b0 = static_cast<const char *>(lanes[b].ws_dev), *b1 = b0 + lanes[b].ws_bytes;
+            if (b0 && a0 < b1 && b0 < a1) return QP_EINVAL;
+        }
+    }
+    // every job is checked before the first is launched
+    for (uint32_t i = 0; i < count; ++i) {
+        const qp_job_t &j = jobs[i];
+        const qp_lane_t &l = lanes[i % n_lanes];
+        if (j.dtype != (uint32_t)QP_F32 && j.dtype != (uint32_t)QP_BF16) return QP_EINVAL;
+        const qp_status st = check_compress(j.x_dev, j.n, (qp_dtype)j.dtype, j.bits, cfg, l.ws_dev, l.ws_bytes, j.packed_dev,
+                                            (size_t)j.packed_bytes);
+        if (st != QP_OK) return st;
+        // a later job of this call overwrites the lane's records: this one's grid must leave the workspace
+        if ((uint64_t)i + n_lanes < count && !j.qparams_out_dev) return QP_EINVAL;
+    }
+    for (uint32_t i = 0; i < count; ++i) {
+        const qp_job_t &j = jobs[i];
+        const qp_lane_t &l = lanes[i % n_lanes];
+        const qp_status st = qp_compress_async(j.x_dev, j.n, (qp_dtype)j.dtype, j.bits, cfg, l.ws_dev, l.ws_bytes, j.packed_dev,
+                                               (size_t)j.packed_bytes, j.qparams_out_dev, l.stream);
+        if (st != QP_OK) return st;
+    }
     return QP_OK;
 }
 

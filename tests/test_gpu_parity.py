@@ -1051,6 +1051,50 @@ def test_two_streams_with_their_own_workspaces(qp):
         assert (bytes(qp.read_ws(wa, qp.QP_WS_RESULT, qp.qp_search_result_t)), bytes(qp.read_ws(wb, qp.QP_WS_RESULT, qp.qp_search_result_t))) == ref
 
 
+def test_many_tensors_in_flight_match_the_single_calls(qp):
+    """qp_compress_many_async: seven tensors of mixed size, dtype and bitwidth (tile search, streaming search, value table)
+    over three lanes; every payload and grid record equals what qp_compress_async leaves for that tensor alone, and each
+    lane's workspace ends with the records of its last job."""
+    specs = [("C2", 700_001, 4), ("C5", 1_300_003, 3), ("C3", 2_500_003, 2), ("C1", None, 8), ("C2", 5, 16), ("C5", 300_001, 6),
+             ("C4", 2_200_001, 4)]
+    xs = [si.make_config(name, n=n) for name, n, _ in specs]
+    ds = [to_dev(x) for x in xs]
+    nmax = max(x.size for x in xs)
+    ws1 = qp.alloc_workspace(nmax)
+    ref = []
+    for d, (_, _, bits) in zip(ds, specs):
+        pk = qp.alloc_packed(d.numel(), bits)
+        qp.qp_compress_async(d, bits, ws1, pk)
+        torch.cuda.synchronize()
+        ref.append((pk, bytes(qp.read_ws(ws1, qp.QP_WS_QPARAMS, qp.qp_qparams_t)),
+                    bytes(qp.read_ws(ws1, qp.QP_WS_RESULT, qp.qp_search_result_t))))
+    lanes = [(qp.alloc_workspace(nmax), torch.cuda.Stream()) for _ in range(3)]
+    for w, _ in lanes:
+        w.fill_(0x77)
+    for rep in range(3):
+        pks = [qp.alloc_packed(d.numel(), bits) for d, (_, _, bits) in zip(ds, specs)]
+        qrecs = torch.zeros(len(specs) * 32, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        jobs = [(d, bits, pk, qrecs.data_ptr() + 32 * k) for k, (d, (_, _, bits), pk) in enumerate(zip(ds, specs, pks))]
+        qp.qp_compress_many_async(jobs, lanes)
+        torch.cuda.synchronize()
+        q_host = qrecs.cpu().numpy().tobytes()
+        for k in range(len(specs)):
+            assert torch.equal(pks[k], ref[k][0]), (rep, k)
+            assert q_host[32 * k:32 * k + 32] == ref[k][1], (rep, k)
+        for lane, last in ((0, 6), (1, 4), (2, 5)):
+            assert bytes(qp.read_ws(lanes[lane][0], qp.QP_WS_RESULT, qp.qp_search_result_t)) == ref[last][2], (rep, lane)
+    # the last jobs of the lanes may leave their grids in the workspace only
+    jobs[4] = jobs[4][:3] + (0,)
+    jobs[6] = jobs[6][:3] + (0,)
+    qp.qp_compress_many_async(jobs, lanes)
+    torch.cuda.synchronize()
+    assert bytes(qp.read_ws(lanes[0][0], qp.QP_WS_QPARAMS, qp.qp_qparams_t)) == ref[6][1]
+    jobs[0] = jobs[0][:3] + (0,)
+    with pytest.raises(qp.QuantPipeError):
+        qp.qp_compress_many_async(jobs, lanes)
+
+
 @pytest.mark.timeout(600)
 def test_timed_step_spread_over_four_streams(qp):
     """The launch configuration bench.py times: the six passes of a step over the full C2 tensor handed round-robin to four

@@ -54,6 +54,41 @@ def test_no_alloc_entry_point_refuses_before_touching_the_gpu(qp):
     assert L.qp_compress_noalloc(fake, 1000, 0, 4, None, fake, big, None, None) == qp.QP_EINVAL
 
 
+def test_many_tensor_entry_point_checks_every_job_before_touching_the_gpu(qp):
+    """Bad lanes, overlapping workspaces and a bad job anywhere in the list are refused by checks that precede every HIP
+    call (the pointers here are not device memory: a launch would fail differently)."""
+    L = qp.lib()
+    need = qp.qp_workspace_bytes(1000)
+    pk = qp.qp_packed_bytes(1000, 4)
+    assert C.sizeof(qp.qp_job_t) == 48 and C.sizeof(qp.qp_lane_t) == 24
+
+    def job(x=0x10000, n=1000, dtype=0, bits=4, packed=0x20000, packed_bytes=pk, q=0x30000):
+        return qp.qp_job_t(x, n, dtype, bits, packed, packed_bytes, q)
+
+    def call(jobs, lanes, count=None, n_lanes=None):
+        ja = (qp.qp_job_t * max(1, len(jobs)))(*jobs)
+        la = (qp.qp_lane_t * max(1, len(lanes)))(*lanes)
+        return L.qp_compress_many_async(ja, len(jobs) if count is None else count, None, la,
+                                        len(lanes) if n_lanes is None else n_lanes)
+
+    two = [qp.qp_lane_t(0x100000, need, None), qp.qp_lane_t(0x100000 + need, need, None)]
+    good = [job(), job(), job()]
+    assert L.qp_compress_many_async(None, 1, None, (qp.qp_lane_t * 2)(*two), 2) == qp.QP_EINVAL
+    assert L.qp_compress_many_async((qp.qp_job_t * 3)(*good), 3, None, None, 2) == qp.QP_EINVAL
+    assert call(good, two, count=0) == qp.QP_EINVAL
+    assert call(good, two, n_lanes=0) == qp.QP_EINVAL
+    assert call(good, two * 40) == qp.QP_EINVAL                                        # more than 64 lanes
+    assert call(good, [two[0], qp.qp_lane_t(0x100000 + need - 16, need, None)]) == qp.QP_EINVAL   # workspaces overlap
+    assert call(good, [two[0], qp.qp_lane_t(None, need, None)]) == qp.QP_EINVAL
+    assert call(good, [two[0], qp.qp_lane_t(0x100000 + need, need - 16, None)]) == qp.QP_ENOSPC   # lane 1 too small for job 1
+    assert call([job(), job(), job(bits=5)], two) == qp.QP_EINVAL                      # the last job is bad: nothing ran
+    assert call([job(), job(dtype=7), job()], two) == qp.QP_EINVAL
+    assert call([job(), job(packed_bytes=pk - 4), job()], two) == qp.QP_ENOSPC
+    assert call([job(x=0x10004), job(), job()], two) == qp.QP_EINVAL                   # misaligned tensor
+    # job 0's lane is reused by job 2, so job 0 needs a place for its grid; jobs 1 and 2 are the last of their lanes
+    assert call([job(q=None), job(), job()], two) == qp.QP_EINVAL
+
+
 def test_struct_sizes_match_the_header_layout(qp):
     assert C.sizeof(qp.qp_stats_t) == 88
     assert C.sizeof(qp.qp_qparams_t) == 32
