@@ -19,8 +19,9 @@
  *     device); pointers named *_host, and all struct pointers unless named *_dev,
  *     are HOST pointers.  The caller owns every buffer.  The library allocates
  *     no device memory and keeps no state between calls except a per-device
- *     cache of one occupancy query; two calls may run concurrently if they use
- *     different streams AND different workspaces.
+ *     cache of one occupancy query (and the static workspace behind
+ *     qp_compress_noalloc, which only that call uses); two calls may run
+ *     concurrently if they use different streams AND different workspaces.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - x_dev, packed_dev, y_dev and ws_dev must be 16-byte aligned; ws_dev needs
  *     qp_workspace_bytes() bytes.  The workspace needs no initialisation.
