@@ -1097,9 +1097,10 @@ def test_many_tensors_in_flight_match_the_single_calls(qp):
 
 @pytest.mark.timeout(600)
 def test_timed_step_spread_over_four_streams(qp):
-    """The launch configuration bench.py times: the six passes of a step over the full C2 tensor handed round-robin to four
-    streams, each with its own workspace, several steps in flight.  Every payload, output and result record equals
-    what the same pass leaves when it runs alone on one stream (whose parity with the oracle the tests above hold)."""
+    """The kind of launch configuration bench.py times (it takes three lanes; four here, so that the lanes carry unequal
+    numbers of passes): the six passes of a step over the full C2 tensor handed round-robin to streams, each with its
+    own workspace, several steps in flight.  Every payload, output and result record equals what the same pass
+    leaves when it runs alone on one stream (whose parity with the oracle the tests above hold)."""
     x = si.make_config("C2")
     n, bits_set = x.size, si.CONFIG_BITS["C2"]
     d = to_dev(x)
